@@ -1,0 +1,148 @@
+/*
+ * bppsa.h - C ABI of the MI355X (gfx950) BPPSA library.
+ *
+ * BPPSA recasts back-propagation as an exclusive scan, under the operator
+ * A <> B = B A, over the array [ g_n, Jt_n, ..., Jt_1 ] of the loss gradient
+ * and the transposed per-step Jacobians (paper Section 3.1, Eq. 4 and Eq. 5),
+ * evaluated by a modified Blelloch up-sweep / down-sweep (Section 3.2,
+ * Algorithm 1).  This header declares the calls of that hot path.
+ *
+ * Conventions shared by every call
+ *   - Every array pointer is a DEVICE pointer to memory owned by the caller
+ *     (fp32 values, int32 indices), C-contiguous in the stated shape.  The
+ *     library neither frees nor retains caller memory and never modifies an
+ *     input array.
+ *   - Scratch space comes only from the caller's `workspace` (device memory,
+ *     256-byte aligned) whose size the matching *_workspace_bytes query returns.
+ *     A workspace that is too small yields BPPSA_EWORKSPACE and nothing is
+ *     launched.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls enqueue work and return; they do not synchronise.  Launch failures
+ *     are reported as BPPSA_EHIP.
+ *   - Shapes are validated on the host before anything is launched:
+ *     BPPSA_EINVAL for null pointers / non-positive sizes, BPPSA_ESHAPE for
+ *     sizes a kernel cannot take, BPPSA_EOVERFLOW when an index would not fit
+ *     its integer type, BPPSA_EUNSUPPORTED for a cell / size with no kernel.
+ *   - Time indexing: hidden states h[0..T] with h[0] the initial state;
+ *     x[t-1] is the input that produces h[t]; Jt[t] = (d h[t+1] / d h[t])^T for
+ *     t = 0..T-1, so that g[t] = Jt[t] g[t+1] with g[t] = dL/dh[t] (Eq. 3).
+ *     In the paper's array a[0] = g[T] and a[k] = Jt[T-k].
+ */
+#ifndef BPPSA_H
+#define BPPSA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  BPPSA_OK = 0,
+  BPPSA_EINVAL = 1,
+  BPPSA_ESHAPE = 2,
+  BPPSA_EWORKSPACE = 3,
+  BPPSA_EOVERFLOW = 4,
+  BPPSA_EHIP = 5,
+  BPPSA_EUNSUPPORTED = 6
+} bppsa_status;
+
+typedef enum { BPPSA_RNN_TANH = 0, BPPSA_GRU = 1 } bppsa_cell;
+
+/* Human-readable name of a status code (static storage, never NULL). */
+const char* bppsa_strerror(int status);
+
+/* ------------------------------------------------------------------------
+ * Workload preparation (outside the timed hot path).
+ * ---------------------------------------------------------------------- */
+
+/*
+ * Forward recurrence that produces the hidden states the hot path consumes.
+ *   RNN (Section 4.1):  h[t] = tanh(W_ih x[t-1] + b_ih + W_hh h[t-1] + b_hh)
+ *   GRU (Section 4.2):  gates r, z, n in that row order of w_ih [3H,I],
+ *                       w_hh [3H,H], b_ih [3H], b_hh [3H].
+ * h is [T+1,B,H]; h[0] is read as the initial state, h[1..T] are written.
+ * x is [T,B,I].  RNN: w_ih [H,I], w_hh [H,H], b_ih [H], b_hh [H]; either bias
+ * may be NULL (treated as zero).
+ */
+bppsa_status bppsa_forward(int cell, int T, int B, int H, int I,
+                           const float* x, const float* w_ih, const float* w_hh,
+                           const float* b_ih, const float* b_hh,
+                           float* h, void* stream);
+
+/*
+ * Softmax cross-entropy head on the last hidden state, mean over the batch
+ * (Section 4.1): z = W_out h_T + b_out, L = mean_b( logsumexp(z_b) - z_b[y_b] ).
+ * Writes seed[B,H] = dL/dh_T (the a[0] of Eq. 5) and, if loss != NULL, L.
+ * h_last [B,H], w_out [C,H], b_out [C], labels [B] int32 in [0,C).  C <= 64.
+ */
+bppsa_status bppsa_head_seed(int B, int H, int C,
+                             const float* h_last, const float* w_out,
+                             const float* b_out, const int32_t* labels,
+                             float* seed, float* loss, void* stream);
+
+/* ------------------------------------------------------------------------
+ * Hot path.
+ * ---------------------------------------------------------------------- */
+
+/*
+ * Materialise the transposed step Jacobians, the matrix entries of Eq. 5.
+ *   RNN: Jt[t][b][i][j] = W_hh[j][i] * (1 - h[t+1][b][j]^2)   (from the RNN
+ *        equation of Section 4.1); only h and w_hh are read, x / w_ih / b_* may
+ *        be NULL.
+ *   GRU: the gates are recomputed from (h[t], x[t]) for all t in parallel and
+ *        combined as in Appendix E's closed form.
+ * Jt is [T,B,H,H], row-major per matrix, written in full.
+ */
+bppsa_status bppsa_build_jacobians(int cell, int T, int B, int H, int I,
+                                   const float* h, const float* x,
+                                   const float* w_ih, const float* w_hh,
+                                   const float* b_ih, const float* b_hh,
+                                   float* Jt, void* stream);
+
+/* Bytes of workspace bppsa_scan needs for these sizes (host-only, pure). */
+size_t bppsa_scan_workspace_bytes(int T, int B, int H);
+
+/*
+ * The scan of Eq. 4 / Algorithm 1:  G[t-1][b] = dL/dh[t] for t = 1..T given
+ * seed[b] = dL/dh[T], i.e. G[T-1] = seed and G[t-1] = Jt[t] G[t].
+ * If g0 != NULL it receives dL/dh[0] = Jt[0] G[0] (the inclusive tail); with
+ * g0 == NULL Jt[0] is never read (Algorithm 1's last input reaches no output).
+ * Jt [T,B,H,H], seed [B,H], G [T,B,H], g0 [B,H] or NULL.  T = 1 is legal.
+ * Values follow any bracketing of the products (Section 3.5): results agree
+ * with sequential back-propagation up to fp32 rounding order.
+ */
+bppsa_status bppsa_scan(int T, int B, int H,
+                        const float* Jt, const float* seed,
+                        float* G, float* g0,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
+/* Bytes of workspace bppsa_param_grads needs (host-only, pure). */
+size_t bppsa_param_grads_workspace_bytes(int cell, int T, int B, int H, int I);
+
+/*
+ * Parameter gradients, Eq. 2 summed over the steps that share the parameters.
+ *   RNN: delta[t] = (1 - h[t]^2) o G[t-1];  dW_hh = sum delta[t] h[t-1]^T,
+ *        dW_ih = sum delta[t] x[t-1]^T, db = sum delta[t]  (t = 1..T, all b).
+ *        Outputs dW_ih [H,I], dW_hh [H,H], db_ih [H]; db_hh [H] (same values)
+ *        is written when non-NULL.  w_* and b_* inputs are not read.
+ *   GRU: dW_ih [3H,I], dW_hh [3H,H], db_ih [3H], db_hh [3H]; the gates are
+ *        recomputed from (h, x, weights); db_ih and db_hh differ only in the
+ *        n-gate rows.
+ * Outputs are overwritten, not accumulated.  Sums use blocked fp32 partials
+ * reduced in a fixed order (deterministic).
+ */
+bppsa_status bppsa_param_grads(int cell, int T, int B, int H, int I,
+                               const float* h, const float* x, const float* G,
+                               const float* w_ih, const float* w_hh,
+                               const float* b_ih, const float* b_hh,
+                               float* dW_ih, float* dW_hh,
+                               float* db_ih, float* db_hh,
+                               void* workspace, size_t workspace_bytes,
+                               void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BPPSA_H */

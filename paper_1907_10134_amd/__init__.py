@@ -1,0 +1,12 @@
+"""MI355X-native BPPSA hot path: thin Python binding over the C-ABI library.
+
+The functions here only marshal arguments (device pointers, sizes, the current
+HIP stream) into libbppsa.so; every step of the path runs in the library's HIP
+kernels.  There is no CPU fallback: if the library is not built, importing
+`binding` raises.
+"""
+from . import binding  # noqa: F401
+from .binding import (  # noqa: F401
+    BppsaError, RNN_TANH, GRU, forward, head_seed, build_jacobians, scan,
+    scan_workspace_bytes, param_grads, param_grads_workspace_bytes, lib_path,
+)

@@ -1,0 +1,38 @@
+// Internal helpers shared by the HIP translation units of libbppsa (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "bppsa.h"
+
+#define BPPSA_WAVE 64
+
+// Returns BPPSA_EHIP from the enclosing function if the last launch failed.
+#define BPPSA_CHECK_LAUNCH()                                  \
+  do {                                                        \
+    if (hipGetLastError() != hipSuccess) return BPPSA_EHIP;   \
+  } while (0)
+
+#define BPPSA_HIP_TRY(expr)                                   \
+  do {                                                        \
+    if ((expr) != hipSuccess) return BPPSA_EHIP;              \
+  } while (0)
+
+static inline size_t bppsa_align_up(size_t n, size_t a) { return (n + a - 1) / a * a; }
+
+static inline int bppsa_ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+// A product of sizes that must fit a signed 64-bit element count and whose
+// per-array element count must stay below 2^40 (far above 288 GB of fp32).
+static inline bool bppsa_mul_overflows(int64_t a, int64_t b, int64_t c, int64_t d) {
+  const int64_t lim = (int64_t)1 << 40;
+  if (a <= 0 || b <= 0 || c <= 0 || d <= 0) return true;
+  if (a > lim / b) return true;
+  int64_t ab = a * b;
+  if (ab > lim / c) return true;
+  int64_t abc = ab * c;
+  if (abc > lim / d) return true;
+  return false;
+}

@@ -1,0 +1,89 @@
+// bppsa_build_jacobians: materialise Jt[t][b] = (d h[t+1] / d h[t])^T, the
+// matrix entries of the scan's input array (Section 3.1, Eq. 5).
+//
+// RNN (Section 4.1): d h[t+1][j] / d h[t][i] = (1 - h[t+1][j]^2) W_hh[j][i], so
+// the transposed Jacobian is W_hh^T with column j scaled by 1 - h[t+1][j]^2.
+// The kernel is a pure streaming write (4 H^2 bytes out per 4 H bytes in), so
+// each lane produces one 16-byte piece of a row and consecutive lanes write
+// consecutive addresses; W_hh^T sits in LDS.
+#include "bppsa_internal.h"
+
+namespace {
+
+template <int VEC>
+__global__ void __launch_bounds__(256)
+rnn_jacobians_kernel(long long n_vec, int B, int H,
+                     const float* __restrict__ h, const float* __restrict__ w_hh,
+                     float* __restrict__ Jt, int w_in_lds) {
+  extern __shared__ float wt[];  // wt[i*H + j] = W_hh[j][i]
+  if (w_in_lds) {
+    for (int e = threadIdx.x; e < H * H; e += blockDim.x) {
+      const int j = e / H, i = e - j * H;
+      wt[i * H + j] = w_hh[e];
+    }
+    __syncthreads();
+  }
+  const int hv = H / VEC;            // vectors per row
+  const long long mv = (long long)hv * H;  // vectors per matrix
+  const long long stride = (long long)gridDim.x * blockDim.x;
+  for (long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x; e < n_vec; e += stride) {
+    const long long m = e / mv;                 // matrix index t*B + b
+    const int rem = (int)(e - m * mv);
+    const int i = rem / hv;
+    const int j = (rem - i * hv) * VEC;
+    const float* hr = h + (size_t)(m + B) * H + j;  // h[t+1][b][j..]
+    float out[VEC];
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) {
+      const float hj = hr[v];
+      const float w = w_in_lds ? wt[i * H + j + v] : w_hh[(size_t)(j + v) * H + i];
+      out[v] = w * (1.0f - hj * hj);
+    }
+    float* dst = Jt + (size_t)e * VEC;
+    if (VEC == 4) {
+      *reinterpret_cast<float4*>(dst) = make_float4(out[0], out[1], out[2], out[3]);
+    } else {
+#pragma unroll
+      for (int v = 0; v < VEC; ++v) dst[v] = out[v];
+    }
+  }
+}
+
+}  // namespace
+
+bppsa_status bppsa_build_jacobians_gru(int T, int B, int H, int I,
+                                       const float* h, const float* x,
+                                       const float* w_ih, const float* w_hh,
+                                       const float* b_ih, const float* b_hh,
+                                       float* Jt, hipStream_t stream);
+
+extern "C" bppsa_status bppsa_build_jacobians(int cell, int T, int B, int H, int I,
+                                              const float* h, const float* x,
+                                              const float* w_ih, const float* w_hh,
+                                              const float* b_ih, const float* b_hh,
+                                              float* Jt, void* stream) {
+  if (!h || !w_hh || !Jt) return BPPSA_EINVAL;
+  if (T < 1 || B < 1 || H < 1) return BPPSA_EINVAL;
+  if (bppsa_mul_overflows(T, B, H, H)) return BPPSA_EOVERFLOW;
+  hipStream_t s = (hipStream_t)stream;
+  if (cell == BPPSA_GRU) {
+    if (!x || !w_ih || I < 1) return BPPSA_EINVAL;
+    return bppsa_build_jacobians_gru(T, B, H, I, h, x, w_ih, w_hh, b_ih, b_hh, Jt, s);
+  }
+  if (cell != BPPSA_RNN_TANH) return BPPSA_EUNSUPPORTED;
+
+  const long long n_elem = (long long)T * B * H * H;
+  const int w_in_lds = (size_t)H * H * sizeof(float) <= 64 * 1024;
+  const size_t lds = w_in_lds ? (size_t)H * H * sizeof(float) : 0;
+  const int vec = (H % 4 == 0) ? 4 : 1;
+  const long long n_vec = n_elem / vec;
+  long long blocks = (n_vec + 256 * 8 - 1) / (256 * 8);
+  if (blocks > 4096) blocks = 4096;
+  if (blocks < 1) blocks = 1;
+  if (vec == 4)
+    rnn_jacobians_kernel<4><<<(int)blocks, 256, lds, s>>>(n_vec, B, H, h, w_hh, Jt, w_in_lds);
+  else
+    rnn_jacobians_kernel<1><<<(int)blocks, 256, lds, s>>>(n_vec, B, H, h, w_hh, Jt, w_in_lds);
+  BPPSA_CHECK_LAUNCH();
+  return BPPSA_OK;
+}

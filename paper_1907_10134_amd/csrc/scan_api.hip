@@ -1,0 +1,34 @@
+// bppsa_scan entry point: validation, workspace accounting and kernel choice.
+#include "bppsa_internal.h"
+#include "scan_plan.h"
+
+namespace {
+constexpr int kMaxGenericH = 128;  // two H x H fp32 tiles must fit the 160 KB LDS
+
+size_t scan_ws_bytes(int T, int B, int H) {
+  const size_t a = bppsa_generic_scan_ws(T, B, H, 0);
+  const size_t b = bppsa_generic_scan_ws(T, B, H, 1);
+  return (a > b ? a : b) + 256;
+}
+}  // namespace
+
+extern "C" size_t bppsa_scan_workspace_bytes(int T, int B, int H) {
+  if (T < 1 || B < 1 || H < 1 || H > kMaxGenericH) return 0;
+  if (bppsa_mul_overflows(T, B, H, H)) return 0;
+  return scan_ws_bytes(T, B, H);
+}
+
+extern "C" bppsa_status bppsa_scan(int T, int B, int H,
+                                   const float* Jt, const float* seed,
+                                   float* G, float* g0,
+                                   void* workspace, size_t workspace_bytes, void* stream) {
+  if (T < 1 || B < 1 || H < 1) return BPPSA_EINVAL;
+  if (!Jt || !seed || !G) return BPPSA_EINVAL;
+  if (bppsa_mul_overflows(T, B, H, H)) return BPPSA_EOVERFLOW;
+  if (B > 65535) return BPPSA_ESHAPE;            // batch rides on gridDim.y
+  if (H > kMaxGenericH) return BPPSA_EUNSUPPORTED;
+  const size_t need = scan_ws_bytes(T, B, H);
+  if (need > 256 && (!workspace || workspace_bytes < need)) return BPPSA_EWORKSPACE;
+  if (workspace && ((uintptr_t)workspace & 255)) return BPPSA_EINVAL;
+  return bppsa_scan_generic(T, B, H, Jt, seed, G, g0, workspace, (hipStream_t)stream);
+}

@@ -1,0 +1,206 @@
+// Generic (any H <= 128) segmented scan for bppsa_scan.
+//
+// The time axis is cut into segments of S steps.  This is the hybrid schedule
+// the paper itself uses when n is much larger than the number of workers
+// (Section 5.3: a truncated up-sweep, a scan of the partial results, then the
+// down-sweep; Section 3.6: step complexity n/p + log p):
+//   reduce : every interior segment multiplies its S transposed Jacobians into
+//            one H x H total (the matrix-matrix side of the up-sweep);
+//   top    : the segment that touches the seed only ever needs matrix-vector
+//            products (Section 3.1: A may be a vector), so it is applied
+//            directly and hands its last vector on as the next level's seed;
+//   recurse: the totals form a shorter chain of the same kind - scan it;
+//   apply  : every other segment walks its steps with matrix-vector products
+//            from its incoming vector (the down-sweep side).
+// Any bracketing gives the same gradients up to rounding (Section 3.5).
+#include "bppsa_internal.h"
+#include "scan_plan.h"
+
+namespace {
+
+constexpr int kThreads = 256;
+
+// Segment `seg` covers time steps [lo, hi]; it consumes g[hi+1] and yields g[lo..hi].
+__device__ __forceinline__ void seg_bounds(int T, int t_min, int S, int seg, int& lo, int& hi) {
+  lo = t_min + seg * S;
+  hi = min(lo + S, T) - 1;
+}
+
+// Total[seg][b] = Jt[lo] Jt[lo+1] ... Jt[hi], built by left-multiplying from hi down.
+template <int MAXE>
+__global__ void __launch_bounds__(kThreads)
+reduce_segments_kernel(int T, int B, int H, int t_min, int S, int seg_begin,
+                       const float* __restrict__ Jt, float* __restrict__ tot) {
+  extern __shared__ float smem[];
+  const int HH = H * H;
+  float* P = smem;
+  float* J = smem + HH;
+  const int seg = seg_begin + blockIdx.x;
+  const int b = blockIdx.y;
+  int lo, hi;
+  seg_bounds(T, t_min, S, seg, lo, hi);
+  const float* src = Jt + ((size_t)hi * B + b) * HH;
+  for (int e = threadIdx.x; e < HH; e += kThreads) P[e] = src[e];
+  for (int t = hi - 1; t >= lo; --t) {
+    src = Jt + ((size_t)t * B + b) * HH;
+    for (int e = threadIdx.x; e < HH; e += kThreads) J[e] = src[e];
+    __syncthreads();
+    float acc[MAXE];
+#pragma unroll
+    for (int k = 0; k < MAXE; ++k) {
+      const int e = threadIdx.x + k * kThreads;
+      acc[k] = 0.f;
+      if (e < HH) {
+        const int i = e / H, j = e - i * H;
+        float a = 0.f;
+        for (int q = 0; q < H; ++q) a += J[i * H + q] * P[q * H + j];
+        acc[k] = a;
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < MAXE; ++k) {
+      const int e = threadIdx.x + k * kThreads;
+      if (e < HH) P[e] = acc[k];
+    }
+    __syncthreads();
+  }
+  __syncthreads();
+  float* dst = tot + ((size_t)seg * B + b) * HH;
+  for (int e = threadIdx.x; e < HH; e += kThreads) dst[e] = P[e];
+}
+
+// v <- Jt[t] v for t = hi..lo, writing g[t] = v to G[t-1] (or g0 when t == 0).
+// LPR lanes cooperate on one row; the wave reduces their partial sums.
+__global__ void __launch_bounds__(kThreads)
+apply_segments_kernel(int T, int B, int H, int t_min, int S, int seg_begin, int LPR,
+                      const float* __restrict__ Jt,
+                      const float* __restrict__ vin, int vin_is_seed,
+                      float* __restrict__ G, float* __restrict__ g0,
+                      float* __restrict__ v_out) {
+  extern __shared__ float smem[];
+  float* v0 = smem;
+  float* v1 = smem + H;
+  const int seg = seg_begin + blockIdx.x;
+  const int b = blockIdx.y;
+  int lo, hi;
+  seg_bounds(T, t_min, S, seg, lo, hi);
+  const float* vsrc = vin_is_seed ? vin + (size_t)b * H : vin + ((size_t)seg * B + b) * H;
+  for (int e = threadIdx.x; e < H; e += kThreads) v0[e] = vsrc[e];
+  __syncthreads();
+  const int rows_per_pass = kThreads / LPR;
+  const int r = threadIdx.x / LPR;
+  const int l = threadIdx.x - r * LPR;
+  for (int t = hi; t >= lo; --t) {
+    const float* Jm = Jt + ((size_t)t * B + b) * H * H;
+    float* dst = (t >= 1) ? G + ((size_t)(t - 1) * B + b) * H : g0 + (size_t)b * H;
+    for (int i0 = 0; i0 < H; i0 += rows_per_pass) {
+      const int i = i0 + r;
+      float part = 0.f;
+      if (i < H) {
+        const float* row = Jm + (size_t)i * H;
+        for (int j = l; j < H; j += LPR) part += row[j] * v0[j];
+      }
+      for (int m = LPR >> 1; m >= 1; m >>= 1) part += __shfl_xor(part, m);
+      if (i < H && l == 0) {
+        v1[i] = part;
+        dst[i] = part;
+      }
+    }
+    __syncthreads();
+    float* tmp = v0; v0 = v1; v1 = tmp;
+  }
+  if (v_out) {
+    float* d = v_out + (size_t)b * H;
+    for (int e = threadIdx.x; e < H; e += kThreads) d[e] = v0[e];
+  }
+}
+
+__global__ void copy_rows_kernel(long long n, const float* __restrict__ src, float* __restrict__ dst) {
+  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) dst[i] = src[i];
+}
+
+int lanes_per_row(int H) {
+  int cap = kThreads / H;
+  if (cap < 1) cap = 1;
+  if (cap > 64) cap = 64;
+  int lpr = 1;
+  while (lpr * 2 <= cap && lpr < H) lpr *= 2;
+  return lpr;
+}
+
+bppsa_status launch_reduce(int T, int B, int H, int t_min, int S, int seg_begin, int seg_count,
+                           const float* Jt, float* tot, hipStream_t s) {
+  if (seg_count <= 0) return BPPSA_OK;
+  const size_t lds = (size_t)2 * H * H * sizeof(float);
+  dim3 grid(seg_count, B);
+  const int HH = H * H;
+#define BPPSA_LAUNCH_REDUCE(E)                                                              \
+  do {                                                                                      \
+    if (lds > 48 * 1024)                                                                    \
+      BPPSA_HIP_TRY(hipFuncSetAttribute((const void*)reduce_segments_kernel<E>,             \
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)); \
+    reduce_segments_kernel<E><<<grid, kThreads, lds, s>>>(T, B, H, t_min, S, seg_begin, Jt, tot); \
+  } while (0)
+  if (HH <= 2 * kThreads) BPPSA_LAUNCH_REDUCE(2);
+  else if (HH <= 4 * kThreads) BPPSA_LAUNCH_REDUCE(4);
+  else if (HH <= 16 * kThreads) BPPSA_LAUNCH_REDUCE(16);
+  else BPPSA_LAUNCH_REDUCE(64);
+#undef BPPSA_LAUNCH_REDUCE
+  BPPSA_CHECK_LAUNCH();
+  return BPPSA_OK;
+}
+
+bppsa_status launch_apply(int T, int B, int H, int t_min, int S, int seg_begin, int seg_count,
+                          const float* Jt, const float* vin, int vin_is_seed,
+                          float* G, float* g0, float* v_out, hipStream_t s) {
+  if (seg_count <= 0) return BPPSA_OK;
+  dim3 grid(seg_count, B);
+  apply_segments_kernel<<<grid, kThreads, (size_t)2 * H * sizeof(float), s>>>(
+      T, B, H, t_min, S, seg_begin, lanes_per_row(H), Jt, vin, vin_is_seed, G, g0, v_out);
+  BPPSA_CHECK_LAUNCH();
+  return BPPSA_OK;
+}
+
+// One level of the recursion; `ws` is the unused tail of the workspace.
+bppsa_status scan_level(int T, int B, int H, const float* Jt, const float* seed,
+                        float* G, float* g0, char* ws, hipStream_t s) {
+  const size_t row = (size_t)B * H;
+  if (seed != G + (size_t)(T - 1) * row) {
+    const long long n = (long long)row;
+    copy_rows_kernel<<<(int)((n + 255) / 256), 256, 0, s>>>(n, seed, G + (size_t)(T - 1) * row);
+    BPPSA_CHECK_LAUNCH();
+  }
+  const int t_min = g0 ? 0 : 1;
+  const int n = T - t_min;
+  if (n <= 0) return BPPSA_OK;
+  const int S = bppsa_generic_segment(H);
+  if (n <= S) return launch_apply(T, B, H, t_min, n, 0, 1, Jt, seed, 1, G, g0, nullptr, s);
+
+  const int nseg = bppsa_ceil_div(n, S);
+  const int T2 = nseg - 1;                               // length of the chain of totals
+  float* tot = reinterpret_cast<float*>(ws);
+  ws += bppsa_align_up((size_t)T2 * row * H * sizeof(float), 256);
+  float* vin = reinterpret_cast<float*>(ws);
+  ws += bppsa_align_up((size_t)T2 * row * sizeof(float), 256);
+
+  bppsa_status st;
+  // interior segments 1..nseg-2: matrix-matrix totals (segment 0's total reaches no output)
+  st = launch_reduce(T, B, H, t_min, S, 1, nseg - 2, Jt, tot, s);
+  if (st != BPPSA_OK) return st;
+  // seed-side segment: matrix-vector only; its last vector seeds the chain of totals
+  st = launch_apply(T, B, H, t_min, S, nseg - 1, 1, Jt, seed, 1, G, g0, vin + (size_t)(T2 - 1) * row, s);
+  if (st != BPPSA_OK) return st;
+  // incoming vectors of segments 0..nseg-2 = scan over the totals
+  st = scan_level(T2, B, H, tot, vin + (size_t)(T2 - 1) * row, vin, nullptr, ws, s);
+  if (st != BPPSA_OK) return st;
+  return launch_apply(T, B, H, t_min, S, 0, nseg - 1, Jt, vin, 0, G, g0, nullptr, s);
+}
+
+}  // namespace
+
+bppsa_status bppsa_scan_generic(int T, int B, int H, const float* Jt, const float* seed,
+                                float* G, float* g0, void* workspace, hipStream_t stream) {
+  return scan_level(T, B, H, Jt, seed, G, g0, static_cast<char*>(workspace), stream);
+}

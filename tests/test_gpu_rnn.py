@@ -1,0 +1,166 @@
+"""GPU parity: RNN hot path (build_jacobians, scan, param_grads) through the C ABI
+against the fp64 oracle, element by element on the same seeded inputs."""
+import numpy as np
+import pytest
+
+import workloads
+from oracle import rnn as orn
+from oracle import scan as oscan
+from util import TOL, per_step_err, rel_err, to_gpu, to_np
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def bp():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    import paper_1907_10134_amd as lib
+    return lib
+
+
+def _gpu_forward(bp, w):
+    import torch
+    T, B, H = w["T"], w["B"], w["H"]
+    h = torch.zeros((T + 1, B, H), dtype=torch.float32, device="cuda")
+    bp.forward(bp.RNN_TANH, to_gpu(w["x"]), to_gpu(w["w_ih"]), to_gpu(w["w_hh"]), to_gpu(w["b"]), None, h)
+    return h
+
+
+@pytest.mark.parametrize("T,B,H,I", [(16, 2, 20, 1), (5, 3, 7, 2), (33, 1, 32, 3), (9, 2, 1, 1)])
+def test_forward_and_head_match_oracle(bp, T, B, H, I):
+    w = workloads.rnn_inputs(T, B, H, I, 10, seed=3)
+    h = _gpu_forward(bp, w)
+    h_ref = orn.forward(w["x"], w["w_ih"], w["w_hh"], w["b"])
+    assert rel_err(to_np(h), h_ref) <= 1e-5
+    seed, loss = bp.head_seed(h[-1].contiguous(), to_gpu(w["w_out"]), to_gpu(w["b_out"]), to_gpu(w["labels"]))
+    l_ref, s_ref = orn.head(to_np(h[-1]), w["w_out"], w["b_out"], w["labels"])
+    assert rel_err(to_np(seed), s_ref) <= 1e-5
+    assert abs(float(loss.item()) - l_ref) <= 1e-5 * abs(l_ref)
+
+
+@pytest.mark.parametrize("T,B,H", [(16, 2, 20), (3, 1, 1), (7, 3, 2), (5, 2, 16), (4, 2, 32),
+                                   (130, 5, 20), (2, 2, 33), (2, 1, 128)])
+def test_build_jacobians_rnn(bp, T, B, H):
+    w = workloads.rnn_inputs(T, B, H, 1, 10, seed=T + H)
+    h32 = orn.forward(w["x"], w["w_ih"], w["w_hh"], w["b"]).astype(np.float32)
+    Jt = bp.build_jacobians(bp.RNN_TANH, to_gpu(h32), w_hh=to_gpu(w["w_hh"]))
+    ref = orn.jacobians_T(h32, w["w_hh"])
+    assert rel_err(to_np(Jt), ref) <= 1e-6
+
+
+SCAN_SHAPES = [(1, 2, 20), (2, 2, 20), (3, 1, 5), (63, 2, 20), (64, 2, 20), (65, 3, 20), (66, 1, 20),
+               (127, 2, 16), (128, 2, 20), (129, 2, 20), (130, 16, 20), (200, 2, 32), (257, 3, 1),
+               (300, 2, 2), (70, 2, 33), (131, 1, 64), (67, 2, 128), (1000, 16, 20), (4300, 2, 20)]
+
+
+@pytest.mark.parametrize("T,B,H", SCAN_SHAPES)
+@pytest.mark.parametrize("want_g0", [False, True])
+def test_scan_matches_linear_scan(bp, T, B, H, want_g0):
+    import torch
+    if T >= 1000:
+        jt, seed = workloads.reflection_jacobian_chain(T, B, H, seed=T * 131 + H)
+    else:
+        jt, seed = workloads.random_jacobian_chain(T, B, H, seed=T * 131 + H, scale=1.05 / np.sqrt(H))
+    G_ref, g0_ref = oscan.linear_scan(jt, seed)
+    g0 = torch.empty((B, H), dtype=torch.float32, device="cuda") if want_g0 else None
+    G = bp.scan(to_gpu(jt), to_gpu(seed), g0=g0)
+    torch.cuda.synchronize()
+    assert rel_err(to_np(G), G_ref) <= TOL
+    assert per_step_err(to_np(G), G_ref) <= 20 * TOL
+    assert np.array_equal(to_np(G[T - 1]), seed)
+    if want_g0:
+        assert rel_err(to_np(g0), g0_ref) <= TOL * max(1.0, np.max(np.abs(G_ref)) / np.max(np.abs(g0_ref)))
+
+
+def test_scan_does_not_modify_inputs_and_is_repeatable(bp):
+    import torch
+    jt, seed = workloads.random_jacobian_chain(333, 4, 20, seed=9)
+    djt, dseed = to_gpu(jt), to_gpu(seed)
+    G1 = to_np(bp.scan(djt, dseed))
+    G2 = to_np(bp.scan(djt, dseed))
+    assert np.array_equal(to_np(djt), jt) and np.array_equal(to_np(dseed), seed)
+    assert np.array_equal(G1, G2)
+
+
+def test_scan_identity_and_diagonal_special_cases(bp):
+    T, B, H = 150, 2, 20
+    eye = np.broadcast_to(np.eye(H, dtype=np.float32), (T, B, H, H)).copy()
+    seed = np.random.default_rng(0).standard_normal((B, H)).astype(np.float32)
+    G = to_np(bp.scan(to_gpu(eye), to_gpu(seed)))
+    assert all(np.array_equal(G[t], seed) for t in range(T))
+    d = np.random.default_rng(1).uniform(0.9, 1.1, size=(T, B, H)).astype(np.float32)
+    jt = np.zeros((T, B, H, H), np.float32)
+    jt[..., np.arange(H), np.arange(H)] = d
+    G = to_np(bp.scan(to_gpu(jt), to_gpu(seed)))
+    cp = np.cumprod(d.astype(np.float64)[::-1], axis=0)[::-1]
+    for t in range(1, T):
+        assert np.allclose(G[t - 1], seed * cp[t], rtol=1e-4)
+
+
+@pytest.mark.parametrize("T,B,H,I", [(16, 2, 20, 1), (1, 1, 1, 1), (37, 3, 7, 2), (1000, 16, 20, 1),
+                                     (40, 2, 32, 3), (9, 2, 64, 1)])
+def test_param_grads_rnn(bp, T, B, H, I):
+    w = workloads.rnn_inputs(T, B, H, I, 10, seed=T)
+    h = orn.forward(w["x"], w["w_ih"], w["w_hh"], w["b"])
+    _, seed = orn.head(h[-1], w["w_out"], w["b_out"], w["labels"])
+    G, _ = orn.backward_chain(h, w["w_hh"], seed)
+    h32, G32 = h.astype(np.float32), G.astype(np.float32)
+    ref = orn.param_grads(h32, w["x"], G32)
+    dW_ih, dW_hh, db, db2 = bp.param_grads(bp.RNN_TANH, to_gpu(h32), to_gpu(w["x"]), to_gpu(G32))
+    assert rel_err(to_np(dW_ih), ref[0]) <= TOL
+    assert rel_err(to_np(dW_hh), ref[1]) <= TOL
+    assert rel_err(to_np(db), ref[2]) <= TOL
+    assert np.array_equal(to_np(db), to_np(db2))
+
+
+def _end_to_end(bp, w, h32=None):
+    """forward -> seed -> build_jacobians -> scan -> param_grads, all on the GPU.
+
+    With h32 given, the hidden states are an input (the same fp32 values the oracle uses).
+    """
+    import torch
+    h = _gpu_forward(bp, w) if h32 is None else to_gpu(h32)
+    seed, _ = bp.head_seed(h[-1].contiguous(), to_gpu(w["w_out"]), to_gpu(w["b_out"]), to_gpu(w["labels"]))
+    Jt = bp.build_jacobians(bp.RNN_TANH, h, w_hh=to_gpu(w["w_hh"]))
+    g0 = torch.empty((w["B"], w["H"]), dtype=torch.float32, device="cuda")
+    G = bp.scan(Jt, seed, g0=g0)
+    grads = bp.param_grads(bp.RNN_TANH, h, to_gpu(w["x"]), G)
+    torch.cuda.synchronize()
+    return to_np(G), to_np(g0), [to_np(g) for g in grads]
+
+
+def _oracle_end_to_end(w, h32=None):
+    h = orn.forward(w["x"], w["w_ih"], w["w_hh"], w["b"]) if h32 is None else h32
+    _, seed = orn.head(h[-1], w["w_out"], w["b_out"], w["labels"])
+    G, g0 = orn.backward_chain(h, w["w_hh"], seed)
+    return G, g0, orn.param_grads(h, w["x"], G)
+
+
+@pytest.mark.parametrize("cfg", [0, 1, 2])
+def test_end_to_end_configs(bp, cfg):
+    w = workloads.config_inputs(cfg)
+    G, g0, grads = _end_to_end(bp, w)
+    G_ref, g0_ref, grads_ref = _oracle_end_to_end(w)
+    assert rel_err(G, G_ref) <= TOL
+    for got, ref in zip(grads[:3], grads_ref):
+        assert rel_err(got, ref) <= TOL
+    # stricter, per time step, wherever the gradient has not underflowed fp32
+    assert per_step_err(G, G_ref, floor=1e-30) <= 50 * TOL
+
+
+@pytest.mark.parametrize("T", [1000, 30000])
+def test_end_to_end_norm_preserving(bp, T):
+    # gradients stay O(1) over the whole sequence, so every time step is a real comparison
+    # (gain 1.1 sits at the edge of chaos, so the forward pass is taken from the oracle and
+    # rounded once: both sides then start from identical fp32 hidden states)
+    w = workloads.rnn_inputs_norm_preserving(T, 16, gain=1.02 if T == 1000 else 1.1)
+    h32 = orn.forward(w["x"], w["w_ih"], w["w_hh"], w["b"]).astype(np.float32)
+    G, g0, grads = _end_to_end(bp, w, h32)
+    G_ref, g0_ref, grads_ref = _oracle_end_to_end(w, h32)
+    n = np.max(np.abs(G_ref.reshape(T, -1)), axis=1)
+    assert n.min() > 1e-4 * n.max(), "test weights let the gradient vanish"
+    assert rel_err(G, G_ref) <= TOL
+    assert per_step_err(G, G_ref) <= 100 * TOL
+    for got, ref in zip(grads[:3], grads_ref):
+        assert rel_err(got, ref) <= TOL

@@ -133,6 +133,21 @@ def random_jacobian_chain(T, B, H, seed=0, scale=None, dtype=np.float32):
     return jt, seed_vec
 
 
+def reflection_jacobian_chain(T, B, H, seed=0, jitter=0.02, dtype=np.float32):
+    """A chain of dense matrices c * (I - 2 v v^T / |v|^2) with c ~ U(1 - jitter, 1 + jitter).
+
+    Each factor is a scaled Householder reflection, so products neither vanish
+    nor overflow over tens of thousands of steps while every entry is non-zero.
+    """
+    rng = _rng(seed)
+    v = rng.standard_normal((T, B, H))
+    v /= np.linalg.norm(v, axis=-1, keepdims=True)
+    c = rng.uniform(1.0 - jitter, 1.0 + jitter, size=(T, B, 1, 1))
+    jt = c * (np.eye(H)[None, None] - 2.0 * v[..., :, None] * v[..., None, :])
+    seed_vec = rng.standard_normal((B, H))
+    return jt.astype(dtype), seed_vec.astype(dtype)
+
+
 # --------------------------------------------------------------------------
 # Pruned VGG-11-style CNN (Section 4.3 stand-in): layer list, weights, masks.
 # --------------------------------------------------------------------------
