@@ -1,0 +1,195 @@
+#!/usr/bin/env python3
+"""Benchmark of the BPPSA hot path on one MI355X.
+
+One "step" = bppsa_build_jacobians + bppsa_scan + bppsa_param_grads on the
+vanilla tanh RNN workload H=20, I=1, T=1000, B=16 (the paper's headline point,
+Section 5.1), with hidden states, inputs and weights already resident in HBM.
+Prints ONE JSON line; see the design doc for how each field is derived.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import statistics
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E bandwidth
+
+
+def scan_algorithmic_bytes(T, B, H):
+    """Each Jacobian read once, each gradient written once, the seed read once."""
+    return T * B * (4 * H * H + 4 * H) + 4 * B * H
+
+
+def prepare(bp, w):
+    """Upload a workload and run the (untimed) forward pass and head on the GPU."""
+    import torch
+    dev = "cuda"
+    t = {k: torch.from_numpy(v).to(dev) for k, v in w.items() if hasattr(v, "dtype")}
+    T, B, H = w["T"], w["B"], w["H"]
+    h = torch.zeros((T + 1, B, H), dtype=torch.float32, device=dev)
+    bp.forward(bp.RNN_TANH, t["x"], t["w_ih"], t["w_hh"], t["b"], None, h)
+    seed, _ = bp.head_seed(h[-1].contiguous(), t["w_out"], t["b_out"], t["labels"])
+    bufs = dict(
+        h=h, x=t["x"], w_hh=t["w_hh"], seed=seed,
+        Jt=torch.empty((T, B, H, H), dtype=torch.float32, device=dev),
+        G=torch.empty((T, B, H), dtype=torch.float32, device=dev),
+        g0=torch.empty((B, H), dtype=torch.float32, device=dev),
+        scan_ws=torch.empty(max(bp.scan_workspace_bytes(T, B, H), 256), dtype=torch.uint8, device=dev),
+        pg_ws=torch.empty(max(bp.param_grads_workspace_bytes(bp.RNN_TANH, T, B, H, w["I"]), 256),
+                          dtype=torch.uint8, device=dev),
+        out=(torch.empty((H, w["I"]), dtype=torch.float32, device=dev),
+             torch.empty((H, H), dtype=torch.float32, device=dev),
+             torch.empty((H,), dtype=torch.float32, device=dev),
+             torch.empty((H,), dtype=torch.float32, device=dev)),
+    )
+    torch.cuda.synchronize()
+    return bufs
+
+
+def time_steps(bp, b, steps, warmup):
+    """Whole-path wall time over exactly `steps` steps plus per-call HIP-event times."""
+    import torch
+
+    def step(ev=None):
+        if ev:
+            ev[0].record()
+        bp.build_jacobians(bp.RNN_TANH, b["h"], w_hh=b["w_hh"], Jt=b["Jt"])
+        if ev:
+            ev[1].record()
+        bp.scan(b["Jt"], b["seed"], G=b["G"], g0=None, workspace=b["scan_ws"])
+        if ev:
+            ev[2].record()
+        bp.param_grads(bp.RNN_TANH, b["h"], b["x"], b["G"], out=b["out"], workspace=b["pg_ws"])
+        if ev:
+            ev[3].record()
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+
+    # per-call durations on the launch stream (HIP events), same number of steps
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(steps)]
+    for e in evs:
+        step(e)
+    torch.cuda.synchronize()
+    parts = {name: statistics.mean(e[i].elapsed_time(e[i + 1]) for e in evs)
+             for i, name in enumerate(("build_jacobians_ms", "scan_ms", "param_grads_ms"))}
+    return wall_ms, parts
+
+
+def time_scan_only(bp, b, steps, warmup):
+    import torch
+    for _ in range(warmup):
+        bp.scan(b["Jt"], b["seed"], G=b["G"], g0=None, workspace=b["scan_ws"])
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    for a, z in evs:
+        a.record()
+        bp.scan(b["Jt"], b["seed"], G=b["G"], g0=None, workspace=b["scan_ws"])
+        z.record()
+    torch.cuda.synchronize()
+    return statistics.mean(a.elapsed_time(z) for a, z in evs)
+
+
+def cpu_baseline(w, budget_s=15.0):
+    """The fp64 oracle's backward (chain + parameter sums) on the same workload, one thread."""
+    import numpy as np
+    from threadpoolctl import threadpool_limits
+    from oracle import rnn as orn
+    with threadpool_limits(limits=1):
+        h = orn.forward(w["x"], w["w_ih"], w["w_hh"], w["b"])
+        _, seed = orn.head(h[-1], w["w_out"], w["b_out"], w["labels"])
+        times = []
+        t_start = time.perf_counter()
+        while len(times) < 20 and (time.perf_counter() - t_start) < budget_s:
+            t0 = time.perf_counter()
+            G, _ = orn.backward_chain(h, w["w_hh"], seed)
+            orn.param_grads(h, w["x"], G)
+            times.append((time.perf_counter() - t0) * 1e3)
+    return statistics.median(times), len(times)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--no-long", action="store_true", help="skip the T=30000 scan figure")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding, no collectives); "
+              "use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import workloads
+    import paper_1907_10134_amd as bp
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+
+    w = workloads.config_inputs(1)
+    T, B, H = w["T"], w["B"], w["H"]
+    bufs = prepare(bp, w)
+    wall_ms, parts = time_steps(bp, bufs, args.steps, args.warmup)
+
+    scan_bytes = scan_algorithmic_bytes(T, B, H)
+    scan_gbps = scan_bytes / (parts["scan_ms"] * 1e-3) / 1e9
+    out = {
+        "metric": "backward_pass_ms (build_jacobians + scan + param_grads), RNN H=20 B=16 T=1000",
+        "value": round(wall_ms, 5),
+        "unit": "ms",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(wall_ms, 5),
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": "rnn_tanh_H20_I1_T1000_B16 (configs[1])", "T": T, "B": B, "H": H,
+                   "parallelism": "single-gpu"},
+        "breakdown_ms": {k: round(v, 5) for k, v in parts.items()},
+        "scan_gbps": round(scan_gbps, 2),
+        "roofline": {"kernel": "bppsa_scan", "bound": "hbm", "achieved": round(scan_gbps, 2),
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(scan_gbps / HBM_PEAK_GBPS, 5),
+                     "traffic": None, "algorithmic_bytes": scan_bytes},
+    }
+
+    if not args.no_long:
+        del bufs
+        torch.cuda.empty_cache()
+        w2 = workloads.config_inputs(2)
+        b2 = prepare(bp, w2)
+        bp.build_jacobians(bp.RNN_TANH, b2["h"], w_hh=b2["w_hh"], Jt=b2["Jt"])
+        ms = time_scan_only(bp, b2, steps=max(5, min(50, args.steps)), warmup=3)
+        nbytes = scan_algorithmic_bytes(w2["T"], w2["B"], w2["H"])
+        gbps = nbytes / (ms * 1e-3) / 1e9
+        out["long_scan"] = {"workload": "rnn_tanh_H20_I1_T30000_B16 (configs[2])", "scan_ms": round(ms, 5),
+                            "algorithmic_bytes": nbytes, "gbps": round(gbps, 2),
+                            "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 5)}
+        del b2
+
+    if not args.no_cpu:
+        ms, reps = cpu_baseline(w)
+        out["cpu_baseline"] = {"value": round(ms, 4), "unit": "ms", "cores": 1, "kind": "oracle",
+                               "sample": "full configs[1] workload (T=1000, B=16): fp64 sequential chain + "
+                                         "parameter sums, median of %d passes, numpy limited to one thread" % reps}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
