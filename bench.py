@@ -101,6 +101,19 @@ def time_scan_only(bp, b, steps, warmup):
     return statistics.mean(a.elapsed_time(z) for a, z in evs)
 
 
+def long_scan(bp, workloads, steps):
+    """bppsa_scan alone on configs[2] (T=30000): the HBM-bound case of the scan."""
+    w2 = workloads.config_inputs(2)
+    b2 = prepare(bp, w2)
+    bp.build_jacobians(bp.RNN_TANH, b2["h"], w_hh=b2["w_hh"], Jt=b2["Jt"])
+    ms = time_scan_only(bp, b2, steps=max(5, min(50, steps)), warmup=3)
+    nbytes = scan_algorithmic_bytes(w2["T"], w2["B"], w2["H"])
+    gbps = nbytes / (ms * 1e-3) / 1e9
+    return {"workload": "rnn_tanh_H20_I1_T30000_B16 (configs[2])", "scan_ms": round(ms, 5),
+            "algorithmic_bytes": nbytes, "gbps": round(gbps, 2),
+            "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 5)}
+
+
 def cpu_baseline(w, budget_s=15.0):
     """The fp64 oracle's backward (chain + parameter sums) on the same workload, one thread."""
     import numpy as np
@@ -126,6 +139,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-long", action="store_true", help="skip the T=30000 scan figure")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--long-only", action="store_true",
+                    help="time only the T=30000 scan (for profiling); prints its JSON object")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); "
@@ -139,6 +154,10 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
+
+    if args.long_only:
+        print(json.dumps(long_scan(bp, workloads, args.steps)))
+        return
 
     w = workloads.config_inputs(1)
     T, B, H = w["T"], w["B"], w["H"]
@@ -172,16 +191,7 @@ def main():
     if not args.no_long:
         del bufs
         torch.cuda.empty_cache()
-        w2 = workloads.config_inputs(2)
-        b2 = prepare(bp, w2)
-        bp.build_jacobians(bp.RNN_TANH, b2["h"], w_hh=b2["w_hh"], Jt=b2["Jt"])
-        ms = time_scan_only(bp, b2, steps=max(5, min(50, args.steps)), warmup=3)
-        nbytes = scan_algorithmic_bytes(w2["T"], w2["B"], w2["H"])
-        gbps = nbytes / (ms * 1e-3) / 1e9
-        out["long_scan"] = {"workload": "rnn_tanh_H20_I1_T30000_B16 (configs[2])", "scan_ms": round(ms, 5),
-                            "algorithmic_bytes": nbytes, "gbps": round(gbps, 2),
-                            "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 5)}
-        del b2
+        out["long_scan"] = long_scan(bp, workloads, args.steps)
 
     if not args.no_cpu:
         ms, reps = cpu_baseline(w)

@@ -67,15 +67,21 @@ rnn_param_partials_kernel(long long rows, int B, int H, int I, int rows_per_bloc
   }
 }
 
-__global__ void rnn_param_finish_kernel(int nblocks, int H, int I, const float* __restrict__ part,
-                                        float* __restrict__ dW_ih, float* __restrict__ dW_hh,
-                                        float* __restrict__ db_ih, float* __restrict__ db_hh) {
+// One wave per output element: lanes add the per-block partials in a fixed
+// strided order, then the wave reduces (deterministic).
+__global__ void __launch_bounds__(256)
+rnn_param_finish_kernel(int nblocks, int H, int I, const float* __restrict__ part,
+                        float* __restrict__ dW_ih, float* __restrict__ dW_hh,
+                        float* __restrict__ db_ih, float* __restrict__ db_hh) {
   const int W = H + I + 1;
   const int E = H * W;
-  const int e = blockIdx.x * blockDim.x + threadIdx.x;
-  if (e >= E) return;
+  const int lane = threadIdx.x & 63;
+  const int e = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  if (e >= E) return;                       // whole wave leaves together
   float s = 0.f;
-  for (int k = 0; k < nblocks; ++k) s += part[(size_t)k * E + e];
+  for (int k = lane; k < nblocks; k += 64) s += part[(size_t)k * E + e];
+  for (int m = 32; m >= 1; m >>= 1) s += __shfl_xor(s, m);
+  if (lane != 0) return;
   const int i = e / W, c = e - i * W;
   if (c < H) dW_hh[(size_t)i * H + c] = s;
   else if (c < H + I) dW_ih[(size_t)i * I + (c - H)] = s;
@@ -149,7 +155,7 @@ extern "C" bppsa_status bppsa_param_grads(int cell, int T, int B, int H, int I,
 #undef BPPSA_LAUNCH_PARTIALS
   BPPSA_CHECK_LAUNCH();
   // blocks past the last row range wrote zeros, so summing all nb partials is exact
-  rnn_param_finish_kernel<<<bppsa_ceil_div(E, 256), 256, 0, s>>>(nb, H, I, part, dW_ih, dW_hh, db_ih, db_hh);
+  rnn_param_finish_kernel<<<bppsa_ceil_div(E, 4), 256, 0, s>>>(nb, H, I, part, dW_ih, dW_hh, db_ih, db_hh);
   BPPSA_CHECK_LAUNCH();
   return BPPSA_OK;
 }
