@@ -142,6 +142,124 @@ bppsa_status bppsa_param_grads(int cell, int T, int B, int H, int I,
                                void* workspace, size_t workspace_bytes,
                                void* stream);
 
+
+/* ------------------------------------------------------------------------
+ * Sparse path: CSR transposed Jacobians of a (pruned) CNN and their scan.
+ * ---------------------------------------------------------------------- */
+
+/*
+ * A CSR matrix in the SciPy convention used by Appendix D: row i owns
+ * indices[indptr[i] .. indptr[i+1]) (ascending) and the matching data.  A
+ * transposed Jacobian (d out / d in)^T has rows = input elements and
+ * cols = output elements.  The struct itself lives in HOST memory; the three
+ * arrays are DEVICE pointers.
+ */
+typedef struct {
+  int32_t rows, cols;
+  int64_t nnz;
+  const int32_t* indptr;  /* [rows + 1] */
+  const int32_t* indices; /* [nnz] */
+  const float* data;      /* [nnz] */
+} bppsa_csr;
+
+/*
+ * Appendix D.1: transposed Jacobian of a 3x3, padding-1, stride-1 convolution
+ * (cross-correlation) with weight [co,ci,3,3] on a ci x h x w input.
+ * Row (ci,y,x) holds, per output channel and per in-image neighbour
+ * (y+dy, x+dx), dy,dx in {-1,0,1}, column co*h*w + (y+dy)*w + (x+dx) with value
+ * weight[co][ci][1-dy][1-dx]; columns ascend.  Only in-image neighbours are
+ * stored (nnz = ci*co*(3h-2)(3w-2) unpruned, the count behind Table 1's 0.99157).
+ * `mask` ([co,ci,3,3] bytes, NULL = all kept) marks pruned weights (0) as
+ * structurally absent; a kept weight whose value is 0.0 stays.
+ * Two calls: *_indptr writes indptr[ci*h*w + 1]; the caller reads its last
+ * entry (= nnz) to size indices/data, then *_fill writes them.
+ */
+bppsa_status bppsa_csr_conv3x3_indptr(int ci, int co, int h, int w, const uint8_t* mask,
+                                      int32_t* indptr, void* stream);
+bppsa_status bppsa_csr_conv3x3_fill(int ci, int co, int h, int w, const float* weight,
+                                    const uint8_t* mask, const int32_t* indptr,
+                                    int32_t* indices, float* data, void* stream);
+
+/*
+ * Appendix D.2 (Algorithms 5-7): ReLU on d elements.  indptr[i] = i,
+ * indices[i] = i, data[i] = (x[i] > 0) ? 1 : 0 (explicit zeros are kept).
+ * indptr [d+1], indices [d], data [d].
+ */
+bppsa_status bppsa_csr_relu(int d, const float* x, int32_t* indptr, int32_t* indices,
+                            float* data, void* stream);
+
+/*
+ * Appendix D.3 (Algorithms 8-10): 2x2 / stride-2 max-pooling of x [c,h,w] (h, w
+ * even).  One unit entry per output: row = the window's first maximum in
+ * row-major window order, column = the output's flat index.  indptr [c*h*w+1],
+ * indices and data [c*(h/2)*(w/2)].
+ */
+bppsa_status bppsa_csr_maxpool2x2(int c, int h, int w, const float* x, int32_t* indptr,
+                                  int32_t* indices, float* data, void* stream);
+
+/*
+ * Fully connected layer y = W x with W [out,in]: the transposed Jacobian is W^T
+ * (rows = inputs, cols = outputs) restricted to the kept weights.  Two calls as
+ * for the convolution; indptr is [in + 1].
+ */
+bppsa_status bppsa_csr_linear_indptr(int out, int in, const uint8_t* mask, int32_t* indptr,
+                                     void* stream);
+bppsa_status bppsa_csr_linear_fill(int out, int in, const float* weight, const uint8_t* mask,
+                                   const int32_t* indptr, int32_t* indices, float* data,
+                                   void* stream);
+
+/* y[rows] = A x[cols]: the matrix-vector form of A <> B (Section 3.1). */
+bppsa_status bppsa_spmv(const bppsa_csr* A, const float* x, float* y, void* stream);
+
+/*
+ * Sparse scan (Section 3.3, Section 5.3).  Jt[0..n) are the transposed
+ * Jacobians in SCAN ORDER: Jt[0] belongs to the last layer and
+ * rows(Jt[k]) = cols(Jt[k+1]).  seed has cols(Jt[0]) entries.  On return
+ * grads[k] (caller-allocated, rows(Jt[k]) floats) = Jt[k] ... Jt[0] seed, the
+ * gradient with respect to the input of that layer, for k = 0..n-1; a NULL
+ * entry is skipped (grads[n-1] is the inclusive tail Algorithm 1 does not
+ * produce and costs one extra matrix-vector product).
+ *
+ * The schedule is Algorithm 1's with only `up_levels` up-sweep levels, a linear
+ * scan of the block totals, and the matching down-sweep levels (Section 5.3);
+ * up_levels = 0 is the pure matrix-vector chain.  Products that contain the
+ * gradient vector are CSR x vector, all others CSR x CSR with the structural
+ * pattern (boolean product of the patterns, ascending columns, explicit zeros
+ * kept).
+ *
+ * The index structure of every product depends only on the input patterns, so
+ * it is computed once, ahead of the training loop, by bppsa_spscan_plan_create
+ * (which reads only indptr/indices, synchronises the stream, and carves all
+ * device storage for product structures, product values and intermediate
+ * vectors from `arena`; BPPSA_EWORKSPACE if it does not fit).  The plan itself
+ * is a small host object.  bppsa_spscan_run then only computes values and does
+ * not synchronise; Jt passed to it must have the patterns the plan was built
+ * from (sizes are checked).  cols(B) of any product must be <= 1048576.
+ */
+typedef struct bppsa_spscan_plan bppsa_spscan_plan;
+
+bppsa_status bppsa_spscan_plan_create(int n, const bppsa_csr* Jt, int up_levels,
+                                      void* arena, size_t arena_bytes, void* stream,
+                                      bppsa_spscan_plan** plan);
+void bppsa_spscan_plan_destroy(bppsa_spscan_plan* plan);
+/* Arena bytes the plan occupies, number of CSR x CSR products, and their structure. */
+size_t bppsa_spscan_plan_arena_used(const bppsa_spscan_plan* plan);
+int bppsa_spscan_plan_num_products(const bppsa_spscan_plan* plan);
+/* Product `idx` = left * right; operand ids < n name Jt[id], ids >= n name product id - n. */
+bppsa_status bppsa_spscan_plan_product(const bppsa_spscan_plan* plan, int idx, bppsa_csr* out,
+                                       int* left_id, int* right_id);
+/* Floating-point operations (2 per multiply-add) of the planned matrix-matrix and
+   matrix-vector steps: the static analysis of Section 4.3. */
+bppsa_status bppsa_spscan_plan_flops(const bppsa_spscan_plan* plan, int64_t* mm_flops,
+                                     int64_t* mv_flops);
+
+bppsa_status bppsa_spscan_run(const bppsa_spscan_plan* plan, const bppsa_csr* Jt,
+                              const float* seed, float* const* grads, void* stream);
+
+/* One-shot convenience: plan (in `workspace`), run, destroy.  Synchronises. */
+bppsa_status bppsa_spscan(int n, const bppsa_csr* Jt, const float* seed, float* const* grads,
+                          int up_levels, void* workspace, size_t workspace_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -21,8 +21,9 @@ a[0] = g_T and a[k] = Jt[T-k].
 Pins (tests/test_oracle_scan.py): H = 1 reduces to numpy's cumulative product;
 identity Jacobians return the seed everywhere; diagonal Jacobians reduce to an
 element-wise cumulative product; `blelloch`, `scan_by_definition` and random
-bracketings agree with `linear_scan` for every n up to 130; the RNN oracle's
-matrix-free chain equals `linear_scan` on its explicit Jacobians.
+bracketings agree with `linear_scan` for every n up to 130 (`blelloch_truncated`
+for every n and every number of up-sweep levels); the RNN oracle's matrix-free
+chain equals `linear_scan` on its explicit Jacobians.
 """
 from __future__ import annotations
 
@@ -118,6 +119,58 @@ def blelloch(a, counts=None):
             a[r] = op(a[l], a[r])
     a[n] = None                                    # symbolic identity
     for d in range(levels - 1, -1, -1):            # down-sweep, operands reversed
+        for l, r in pairs(d):
+            t = a[l]
+            a[l] = a[r]
+            tally("down", a[r], t)
+            a[r] = op(a[r], t)
+    return a
+
+
+def blelloch_truncated(a, up_levels, counts=None):
+    """The hybrid schedule of Section 5.3 on a copy of `a`.
+
+    Only the first `up_levels` up-sweep levels run; the block totals they leave
+    behind are then combined by a linear scan (matrix-vector products only,
+    because the first block holds the gradient vector), which deposits every
+    block's exclusive prefix where the down-sweep expects it; the down-sweep then
+    runs its last `up_levels` levels.  up_levels = 0 is the pure linear scan.
+    """
+    a = list(a)
+    n = len(a) - 1
+    levels = math.ceil(math.log2(n + 1)) if n >= 1 else 0
+    U = max(0, min(up_levels, levels - 1)) if levels >= 1 else 0
+    if counts is not None:
+        counts.update({"up_mm": 0, "up_mv": 0, "linear_mv": 0, "down_mm": 0, "down_mv": 0})
+
+    def tally(phase, x, y):
+        if counts is None or x is None or y is None:
+            return
+        kind = "mm" if (x.ndim == 3 and y.ndim == 3) else "mv"
+        counts[phase + "_" + kind] += 1
+
+    def pairs(d):
+        step, half = 1 << (d + 1), 1 << d
+        i = 0
+        while i <= n - half:
+            yield i + half - 1, min(i + step - 1, n)
+            i += step
+
+    for d in range(0, U):
+        for l, r in pairs(d):
+            tally("up", a[l], a[r])
+            a[r] = op(a[l], a[r])
+    block = 1 << U
+    prefix = None                                  # exclusive prefix of the current block
+    for i in range(0, n + 1, block):
+        r = min(i + block - 1, n)
+        total = a[r]
+        a[r] = prefix
+        if i + block <= n:                         # a later block needs prefix <> total
+            if prefix is not None:
+                tally("linear", prefix, total)
+            prefix = op(prefix, total)
+    for d in range(U - 1, -1, -1):
         for l, r in pairs(d):
             t = a[l]
             a[l] = a[r]

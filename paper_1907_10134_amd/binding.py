@@ -48,7 +48,49 @@ def _load():
     lib.bppsa_param_grads_workspace_bytes.argtypes = [c_int] * 5
     lib.bppsa_param_grads.restype = c_int
     lib.bppsa_param_grads.argtypes = [c_int] * 5 + [c_void_p] * 12 + [c_size_t, c_void_p]
+    c_i32p = c_void_p
+    lib.bppsa_csr_conv3x3_indptr.restype = c_int
+    lib.bppsa_csr_conv3x3_indptr.argtypes = [c_int] * 4 + [c_void_p] * 3
+    lib.bppsa_csr_conv3x3_fill.restype = c_int
+    lib.bppsa_csr_conv3x3_fill.argtypes = [c_int] * 4 + [c_void_p] * 6
+    lib.bppsa_csr_relu.restype = c_int
+    lib.bppsa_csr_relu.argtypes = [c_int] + [c_void_p] * 5
+    lib.bppsa_csr_maxpool2x2.restype = c_int
+    lib.bppsa_csr_maxpool2x2.argtypes = [c_int] * 3 + [c_void_p] * 5
+    lib.bppsa_csr_linear_indptr.restype = c_int
+    lib.bppsa_csr_linear_indptr.argtypes = [c_int] * 2 + [c_void_p] * 3
+    lib.bppsa_csr_linear_fill.restype = c_int
+    lib.bppsa_csr_linear_fill.argtypes = [c_int] * 2 + [c_void_p] * 6
+    lib.bppsa_spmv.restype = c_int
+    lib.bppsa_spmv.argtypes = [ctypes.POINTER(CsrDesc), c_void_p, c_void_p, c_void_p]
+    lib.bppsa_spscan_plan_create.restype = c_int
+    lib.bppsa_spscan_plan_create.argtypes = [c_int, ctypes.POINTER(CsrDesc), c_int, c_void_p, c_size_t,
+                                             c_void_p, ctypes.POINTER(c_void_p)]
+    lib.bppsa_spscan_plan_destroy.restype = None
+    lib.bppsa_spscan_plan_destroy.argtypes = [c_void_p]
+    lib.bppsa_spscan_plan_arena_used.restype = c_size_t
+    lib.bppsa_spscan_plan_arena_used.argtypes = [c_void_p]
+    lib.bppsa_spscan_plan_num_products.restype = c_int
+    lib.bppsa_spscan_plan_num_products.argtypes = [c_void_p]
+    lib.bppsa_spscan_plan_product.restype = c_int
+    lib.bppsa_spscan_plan_product.argtypes = [c_void_p, c_int, ctypes.POINTER(CsrDesc),
+                                              ctypes.POINTER(c_int), ctypes.POINTER(c_int)]
+    lib.bppsa_spscan_plan_flops.restype = c_int
+    lib.bppsa_spscan_plan_flops.argtypes = [c_void_p, ctypes.POINTER(ctypes.c_int64),
+                                            ctypes.POINTER(ctypes.c_int64)]
+    lib.bppsa_spscan_run.restype = c_int
+    lib.bppsa_spscan_run.argtypes = [c_void_p, ctypes.POINTER(CsrDesc), c_void_p,
+                                     ctypes.POINTER(c_void_p), c_void_p]
+    lib.bppsa_spscan.restype = c_int
+    lib.bppsa_spscan.argtypes = [c_int, ctypes.POINTER(CsrDesc), c_void_p, ctypes.POINTER(c_void_p),
+                                 c_int, c_void_p, c_size_t, c_void_p]
     return lib
+
+
+class CsrDesc(ctypes.Structure):
+    """Mirror of the C struct bppsa_csr (host struct, device array pointers)."""
+    _fields_ = [("rows", ctypes.c_int32), ("cols", ctypes.c_int32), ("nnz", ctypes.c_int64),
+                ("indptr", ctypes.c_void_p), ("indices", ctypes.c_void_p), ("data", ctypes.c_void_p)]
 
 
 _lib = _load()
@@ -167,3 +209,168 @@ def param_grads(cell, h, x, G, w_ih=None, w_hh=None, b_ih=None, b_hh=None, out=N
                                   workspace.numel() * workspace.element_size(), _stream(stream)),
            "bppsa_param_grads")
     return out
+
+
+# --------------------------------------------------------------------------
+# Sparse path
+# --------------------------------------------------------------------------
+
+class CsrMatrix:
+    """Device CSR arrays (int32 indptr/indices, fp32 data) plus the shape."""
+
+    def __init__(self, rows, cols, indptr, indices, data):
+        self.rows, self.cols = int(rows), int(cols)
+        self.indptr, self.indices, self.data = indptr, indices, data
+        self.nnz = int(indices.numel())
+
+    def desc(self):
+        return CsrDesc(self.rows, self.cols, self.nnz, _ptr(self.indptr, torch.int32),
+                       _ptr(self.indices, torch.int32) if self.nnz else None,
+                       _ptr(self.data) if self.nnz else None)
+
+
+def _i32(n, dev):
+    return torch.empty((max(int(n), 1),), dtype=torch.int32, device=dev)[:int(n)]
+
+
+def _two_call(rows, cols, dev, call_indptr, call_fill):
+    indptr = torch.empty((rows + 1,), dtype=torch.int32, device=dev)
+    call_indptr(indptr)
+    nnz = int(indptr[-1].item())          # the two-call pattern: read nnz, then size the arrays
+    indices = torch.empty((nnz,), dtype=torch.int32, device=dev)
+    data = torch.empty((nnz,), dtype=torch.float32, device=dev)
+    if nnz:
+        call_fill(indptr, indices, data)
+    return CsrMatrix(rows, cols, indptr, indices, data)
+
+
+def csr_conv3x3(weight, mask, h, w, stream=None):
+    """bppsa_csr_conv3x3_indptr + _fill.  weight [co,ci,3,3] fp32, mask same shape uint8 or None."""
+    co, ci = weight.shape[:2]
+    st = _stream(stream)
+    mp = _ptr(mask, torch.uint8, "mask")
+    return _two_call(
+        ci * h * w, co * h * w, weight.device,
+        lambda ip: _check(_lib.bppsa_csr_conv3x3_indptr(ci, co, h, w, mp, _ptr(ip, torch.int32), st),
+                          "bppsa_csr_conv3x3_indptr"),
+        lambda ip, ix, d: _check(_lib.bppsa_csr_conv3x3_fill(ci, co, h, w, _ptr(weight), mp,
+                                                             _ptr(ip, torch.int32), _ptr(ix, torch.int32),
+                                                             _ptr(d), st), "bppsa_csr_conv3x3_fill"))
+
+
+def csr_linear(weight, mask, stream=None):
+    """bppsa_csr_linear_indptr + _fill.  weight [out,in]."""
+    out, inn = weight.shape
+    st = _stream(stream)
+    mp = _ptr(mask, torch.uint8, "mask")
+    return _two_call(
+        inn, out, weight.device,
+        lambda ip: _check(_lib.bppsa_csr_linear_indptr(out, inn, mp, _ptr(ip, torch.int32), st),
+                          "bppsa_csr_linear_indptr"),
+        lambda ip, ix, d: _check(_lib.bppsa_csr_linear_fill(out, inn, _ptr(weight), mp, _ptr(ip, torch.int32),
+                                                            _ptr(ix, torch.int32), _ptr(d), st),
+                                 "bppsa_csr_linear_fill"))
+
+
+def csr_relu(x, stream=None):
+    d = x.numel()
+    dev = x.device
+    indptr = torch.empty((d + 1,), dtype=torch.int32, device=dev)
+    indices = torch.empty((d,), dtype=torch.int32, device=dev)
+    data = torch.empty((d,), dtype=torch.float32, device=dev)
+    _check(_lib.bppsa_csr_relu(d, _ptr(x), _ptr(indptr, torch.int32), _ptr(indices, torch.int32), _ptr(data),
+                               _stream(stream)), "bppsa_csr_relu")
+    return CsrMatrix(d, d, indptr, indices, data)
+
+
+def csr_maxpool2x2(x, stream=None):
+    c, h, w = x.shape
+    dev = x.device
+    n_out = c * (h // 2) * (w // 2)
+    indptr = torch.empty((c * h * w + 1,), dtype=torch.int32, device=dev)
+    indices = torch.empty((n_out,), dtype=torch.int32, device=dev)
+    data = torch.empty((n_out,), dtype=torch.float32, device=dev)
+    _check(_lib.bppsa_csr_maxpool2x2(c, h, w, _ptr(x), _ptr(indptr, torch.int32), _ptr(indices, torch.int32),
+                                     _ptr(data), _stream(stream)), "bppsa_csr_maxpool2x2")
+    return CsrMatrix(c * h * w, n_out, indptr, indices, data)
+
+
+def spmv(A, x, y=None, stream=None):
+    if y is None:
+        y = torch.empty((A.rows,), dtype=torch.float32, device=x.device)
+    d = A.desc()
+    _check(_lib.bppsa_spmv(ctypes.byref(d), _ptr(x), _ptr(y), _stream(stream)), "bppsa_spmv")
+    return y
+
+
+def _desc_array(jts):
+    arr = (CsrDesc * len(jts))()
+    for k, m in enumerate(jts):
+        arr[k] = m.desc()
+    return arr
+
+
+def _grads_array(grads):
+    arr = (ctypes.c_void_p * len(grads))()
+    for k, g in enumerate(grads):
+        arr[k] = None if g is None else _ptr(g)
+    return arr
+
+
+class SpscanPlan:
+    """Host handle of bppsa_spscan_plan_create; device storage lives in `arena` (a uint8 tensor)."""
+
+    def __init__(self, jts, up_levels, arena, stream=None):
+        self.n = len(jts)
+        self.arena = arena
+        self._h = ctypes.c_void_p()
+        descs = _desc_array(jts)
+        _check(_lib.bppsa_spscan_plan_create(self.n, descs, int(up_levels), arena.data_ptr(),
+                                             arena.numel(), _stream(stream), ctypes.byref(self._h)),
+               "bppsa_spscan_plan_create")
+
+    def close(self):
+        if self._h:
+            _lib.bppsa_spscan_plan_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    def __del__(self):
+        self.close()
+
+    def arena_used(self):
+        return int(_lib.bppsa_spscan_plan_arena_used(self._h))
+
+    def num_products(self):
+        return int(_lib.bppsa_spscan_plan_num_products(self._h))
+
+    def flops(self):
+        mm, mv = ctypes.c_int64(), ctypes.c_int64()
+        _check(_lib.bppsa_spscan_plan_flops(self._h, ctypes.byref(mm), ctypes.byref(mv)), "bppsa_spscan_plan_flops")
+        return mm.value, mv.value
+
+    def _view(self, ptr, count, dtype):
+        off = ptr - self.arena.data_ptr()
+        return self.arena[off:off + 4 * count].view(dtype)
+
+    def product(self, idx):
+        """(CsrMatrix view into the arena, left operand id, right operand id)."""
+        d, l, r = CsrDesc(), ctypes.c_int(), ctypes.c_int()
+        _check(_lib.bppsa_spscan_plan_product(self._h, idx, ctypes.byref(d), ctypes.byref(l), ctypes.byref(r)),
+               "bppsa_spscan_plan_product")
+        m = CsrMatrix(d.rows, d.cols, self._view(d.indptr, d.rows + 1, torch.int32),
+                      self._view(d.indices, d.nnz, torch.int32), self._view(d.data, d.nnz, torch.float32))
+        return m, l.value, r.value
+
+    def run(self, jts, seed, grads, stream=None):
+        descs = _desc_array(jts)
+        _check(_lib.bppsa_spscan_run(self._h, descs, _ptr(seed), _grads_array(grads), _stream(stream)),
+               "bppsa_spscan_run")
+        return grads
+
+
+def spscan(jts, seed, grads, up_levels, workspace, stream=None):
+    """bppsa_spscan: one-shot plan + run + destroy (synchronises)."""
+    descs = _desc_array(jts)
+    _check(_lib.bppsa_spscan(len(jts), descs, _ptr(seed), _grads_array(grads), int(up_levels),
+                             workspace.data_ptr(), workspace.numel(), _stream(stream)), "bppsa_spscan")
+    return grads

@@ -1,0 +1,24 @@
+// Internal launchers of the sparse kernels, shared by the builders and the sparse scan.
+#pragma once
+
+#include "bppsa_internal.h"
+
+// In place: a[0..n) holds row lengths on entry, the exclusive prefix sum on exit; a[n] = total.
+bppsa_status bppsa_lengths_to_indptr(int32_t* a, int n, hipStream_t stream);
+
+// y = A x.
+bppsa_status bppsa_launch_spmv(const bppsa_csr& A, const float* x, float* y, hipStream_t stream);
+
+// Structural product C = A B.
+// Pass 1 writes the length of every row of C into c_indptr[0..rows) and adds the number of
+// multiply-adds of the product to *madds (device, 64-bit); the caller turns lengths into
+// row pointers with bppsa_lengths_to_indptr.  Pass 2 writes the ascending column indices.
+bppsa_status bppsa_launch_spgemm_count(const bppsa_csr& A, const bppsa_csr& B, int32_t* c_indptr,
+                                       unsigned long long* madds, hipStream_t stream);
+bppsa_status bppsa_launch_spgemm_indices(const bppsa_csr& A, const bppsa_csr& B, const int32_t* c_indptr,
+                                         int32_t* c_indices, hipStream_t stream);
+// Values of C for a known structure (c_indptr, c_indices); c_data is overwritten.
+bppsa_status bppsa_launch_spgemm_numeric(const bppsa_csr& A, const bppsa_csr& B, const int32_t* c_indptr,
+                                         const int32_t* c_indices, float* c_data, hipStream_t stream);
+
+constexpr int kBppsaMaxSpgemmCols = 1 << 20;  // LDS bitmap: one bit per column of B

@@ -1,0 +1,195 @@
+"""GPU parity: CSR Jacobian builders (bit-exact structure), SpMV, SpGEMM structure and the sparse scan."""
+import numpy as np
+import pytest
+import scipy.sparse as sp
+
+import workloads
+from oracle import cnn as ocnn
+from util import TOL, rel_err, to_gpu, to_np
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def bp():
+    import torch
+    assert torch.cuda.is_available()
+    import paper_1907_10134_amd as lib
+    return lib
+
+
+def _assert_same_csr(got, ref, values=True):
+    """got: binding CsrMatrix on the GPU; ref: scipy CSR from the oracle.  Index arrays bit-exact."""
+    ref = sp.csr_matrix(ref)
+    assert (got.rows, got.cols) == ref.shape
+    assert np.array_equal(to_np(got.indptr), ref.indptr.astype(np.int32))
+    assert np.array_equal(to_np(got.indices), ref.indices.astype(np.int32))
+    if values:
+        d = to_np(got.data)
+        assert d.shape == ref.data.shape
+        if d.size:
+            assert rel_err(d, ref.data) <= 1e-6
+
+
+def _rounded_forward(layers, image):
+    """Oracle forward, then every activation rounded to fp32 once: both sides decide ReLU masks and
+    pooling winners on exactly these values."""
+    acts, _ = ocnn.forward(layers, image)
+    acts32 = [np.asarray(a, np.float32) for a in acts]
+    aux = [ocnn.maxpool2x2_fast(acts32[i].reshape(L.in_shape))[1] if L.kind == "pool" else None
+           for i, L in enumerate(layers)]
+    return acts32, aux
+
+
+def _gpu_jacobians(bp, layers, acts32):
+    """Transposed Jacobians in scan order (last layer first), built on the GPU."""
+    out = []
+    for i in range(len(layers) - 1, -1, -1):
+        L = layers[i]
+        if L.kind == "conv":
+            m = bp.csr_conv3x3(to_gpu(L.weight), to_gpu(L.mask.astype(np.uint8)), L.in_shape[1], L.in_shape[2])
+        elif L.kind == "fc":
+            m = bp.csr_linear(to_gpu(L.weight), to_gpu(L.mask.astype(np.uint8)))
+        elif L.kind == "relu":
+            m = bp.csr_relu(to_gpu(acts32[i].reshape(-1)))
+        else:
+            m = bp.csr_maxpool2x2(to_gpu(acts32[i].reshape(L.in_shape)))
+        out.append(m)
+    return out
+
+
+@pytest.mark.parametrize("ci,co,h,w,keep", [(2, 3, 4, 5, 0.6), (1, 1, 1, 1, 1.0), (3, 2, 2, 2, 0.5), (1, 2, 1, 4, 1.0),
+                                            (3, 64, 32, 32, 1.0), (5, 70, 6, 3, 0.1), (4, 8, 3, 3, 0.0)])
+def test_conv_builder_bit_exact(bp, ci, co, h, w, keep):
+    rng = np.random.default_rng(ci * 100 + co)
+    wt = rng.standard_normal((co, ci, 3, 3)).astype(np.float32)
+    mask = rng.random((co, ci, 3, 3)) < keep if keep < 1.0 else None
+    ref = ocnn.conv_jacobian_T(wt, mask, h, w)
+    got = bp.csr_conv3x3(to_gpu(wt), None if mask is None else to_gpu(mask.astype(np.uint8)), h, w)
+    _assert_same_csr(got, ref)
+    if mask is None:
+        assert got.nnz == ci * co * (3 * h - 2) * (3 * w - 2)      # the count behind Table 1's example
+
+
+def test_relu_pool_linear_builders_bit_exact(bp):
+    rng = np.random.default_rng(1)
+    x = rng.standard_normal((6, 8, 10)).astype(np.float32)
+    x[0, :2, :2] = 0.0
+    x[1, 2:4, 4:6] = 1.5           # ties: the first element of the window wins
+    x[2] = np.maximum(x[2], 0)     # many zero ties, as after a ReLU
+    _assert_same_csr(bp.csr_relu(to_gpu(x.reshape(-1))), ocnn.relu_jacobian_T(x))
+    _, idx = ocnn.maxpool2x2(x)
+    _assert_same_csr(bp.csr_maxpool2x2(to_gpu(x)), ocnn.pool_jacobian_T(idx, x.shape))
+    w = rng.standard_normal((37, 70)).astype(np.float32)
+    m = rng.random((37, 70)) < 0.3
+    _assert_same_csr(bp.csr_linear(to_gpu(w), to_gpu(m.astype(np.uint8))), ocnn.fc_jacobian_T(w, m))
+    _assert_same_csr(bp.csr_linear(to_gpu(w), None), ocnn.fc_jacobian_T(w, None))
+
+
+def test_spmv_matches_scipy(bp):
+    rng = np.random.default_rng(2)
+    for rows, cols, dens in [(50, 70, 0.3), (1000, 300, 0.002), (7, 5, 1.0), (300, 4000, 0.05)]:
+        a = sp.random(rows, cols, density=dens, random_state=rows, format="csr", dtype=np.float32)
+        a.sort_indices()
+        x = rng.standard_normal(cols).astype(np.float32)
+        A = bp.CsrMatrix(rows, cols, to_gpu(a.indptr.astype(np.int32)), to_gpu(a.indices.astype(np.int32)),
+                         to_gpu(a.data))
+        y = to_np(bp.spmv(A, to_gpu(x)))
+        ref = a.astype(np.float64) @ x.astype(np.float64)
+        assert rel_err(y, ref) <= 1e-5 or np.max(np.abs(ref)) == 0
+
+
+def _check_products(bp, plan, jts_ref):
+    """Every planned CSR x CSR product: structure bit-exact against the oracle's structural product."""
+    n = len(jts_ref)
+    mats = list(jts_ref)
+    for k in range(plan.num_products()):
+        got, l, r = plan.product(k)
+        ref = ocnn.csr_product(mats[l], mats[r])
+        mats.append(ref)
+        _assert_same_csr(got, ref, values=False)
+        d = to_np(got.data)
+        if d.size and np.max(np.abs(ref.data)) > 0:
+            assert rel_err(d, ref.data) <= 1e-5
+    return len(mats) - n
+
+
+def _run_spscan(bp, jts, seed, up_levels, n, want_tail=True):
+    import torch
+    arena = torch.empty((1 << 30,), dtype=torch.uint8, device="cuda")
+    plan = bp.SpscanPlan(jts, up_levels, arena)
+    grads = [torch.full((m.rows,), float("nan"), dtype=torch.float32, device="cuda") for m in jts]
+    if not want_tail:
+        grads[-1] = None
+    plan.run(jts, seed, grads)
+    torch.cuda.synchronize()
+    return plan, grads
+
+
+@pytest.mark.parametrize("up_levels", [0, 1, 2, 3, 4, 9])
+def test_spscan_tiny_network(bp, up_levels):
+    layers, image, label = workloads.cnn_layers(conv_channels=(3, 4, 4), pool_after=(1, 3), fc=(6, 5),
+                                                in_shape=(2, 8, 8), prune=0.5, seed=up_levels)
+    acts32, aux = _rounded_forward(layers, image)
+    grads_ref = ocnn.backward(layers, acts32, aux, label)
+    jts_ref = ocnn.network_jacobians_T(layers, acts32, aux)
+    jts = _gpu_jacobians(bp, layers, acts32)
+    for g, r in zip(jts, jts_ref):
+        _assert_same_csr(g, r)
+    n = len(layers)
+    seed = to_gpu(np.asarray(grads_ref[n], np.float32))
+    plan, grads = _run_spscan(bp, jts, seed, up_levels, n, want_tail=(up_levels % 2 == 0))
+    for k in range(n):
+        if grads[k] is None:
+            continue
+        ref = np.asarray(grads_ref[n - 1 - k]).reshape(-1)
+        assert rel_err(to_np(grads[k]), ref) <= TOL, (k, layers[n - 1 - k].kind)
+    nprod = _check_products(bp, plan, jts_ref)
+    assert (nprod == 0) == (up_levels == 0)
+    mm, mv = plan.flops()
+    assert (mm == 0) == (up_levels == 0) and mv > 0
+    plan.close()
+
+
+def test_spscan_one_shot_and_error_paths(bp):
+    import torch
+    layers, image, label = workloads.cnn_layers(conv_channels=(2,), pool_after=(1,), fc=(4, 3),
+                                                in_shape=(1, 4, 4), prune=0.0, seed=3)
+    acts32, aux = _rounded_forward(layers, image)
+    grads_ref = ocnn.backward(layers, acts32, aux, label)
+    jts = _gpu_jacobians(bp, layers, acts32)
+    n = len(layers)
+    seed = to_gpu(np.asarray(grads_ref[n], np.float32))
+    grads = [torch.empty((m.rows,), dtype=torch.float32, device="cuda") for m in jts]
+    ws = torch.empty((1 << 22,), dtype=torch.uint8, device="cuda")
+    bp.spscan(jts, seed, grads, 2, ws)
+    for k in range(n):
+        assert rel_err(to_np(grads[k]), np.asarray(grads_ref[n - 1 - k]).reshape(-1)) <= TOL
+    with pytest.raises(bp.BppsaError) as e:      # arena too small: reported, nothing half-done is returned
+        bp.spscan(jts, seed, grads, 2, ws[:256])
+    assert e.value.code == 3
+    with pytest.raises(bp.BppsaError) as e:      # chain whose shapes do not compose
+        bp.spscan([jts[0], jts[0]], seed, grads[:2], 0, ws)
+    assert e.value.code == 2
+
+
+@pytest.mark.parametrize("up_levels", [0, 2])
+def test_spscan_config4_full_network(bp, up_levels):
+    """configs[4]: the pruned VGG-11-style network on one 32x32x3 image, 26 transposed Jacobians."""
+    layers, image, label = workloads.cnn_layers()
+    acts32, aux = _rounded_forward(layers, image)
+    grads_ref = ocnn.backward(layers, acts32, aux, label)
+    jts_ref = ocnn.network_jacobians_T(layers, acts32, aux)
+    jts = _gpu_jacobians(bp, layers, acts32)
+    assert len(jts) == 26
+    for g, r in zip(jts, jts_ref):
+        _assert_same_csr(g, r)                       # all CSR index structures bit-exact
+    n = len(layers)
+    seed = to_gpu(np.asarray(grads_ref[n], np.float32))
+    plan, grads = _run_spscan(bp, jts, seed, up_levels, n)
+    for k in range(n):
+        ref = np.asarray(grads_ref[n - 1 - k]).reshape(-1)
+        assert rel_err(to_np(grads[k]), ref) <= TOL, (k, layers[n - 1 - k].kind)
+    if up_levels:
+        assert _check_products(bp, plan, jts_ref) > 0
+    plan.close()

@@ -102,3 +102,18 @@ def test_last_jacobian_never_reaches_an_output():
     G1 = scan.from_paper_array(scan.blelloch(scan.to_paper_array(jt, seed)))
     G2 = scan.from_paper_array(scan.blelloch(scan.to_paper_array(jt2, seed)))
     assert np.array_equal(G1, G2)
+
+
+@pytest.mark.parametrize("n", list(range(1, 70)) + [100, 127, 128, 129])
+def test_truncated_schedule_equals_linear_scan_for_every_level_count(n):
+    jt, seed = workloads.random_jacobian_chain(n, 1, 3, seed=300 + n, dtype=np.float64)
+    G, _ = scan.linear_scan(jt, seed)
+    a = scan.to_paper_array(jt, seed)
+    for U in range(0, 9):
+        counts = {}
+        out = scan.blelloch_truncated(a, U, counts)
+        assert out[0] is None
+        assert np.allclose(scan.from_paper_array(out), G, rtol=1e-10, atol=1e-13), (n, U)
+        assert counts["down_mm"] == 0
+        if U == 0:
+            assert counts["up_mm"] == 0 and counts["up_mv"] == 0      # pure linear scan
