@@ -8,7 +8,12 @@ constexpr int kMaxGenericH = 128;  // two H x H fp32 tiles must fit the 160 KB L
 size_t scan_ws_bytes(int T, int B, int H) {
   const size_t a = bppsa_generic_scan_ws(T, B, H, 0);
   const size_t b = bppsa_generic_scan_ws(T, B, H, 1);
-  return (a > b ? a : b) + 256;
+  size_t need = (a > b ? a : b) + 256;
+  if (H == 20) {
+    const size_t c = bppsa_h20_scan_ws(T, B);
+    if (c > need) need = c;
+  }
+  return need;
 }
 }  // namespace
 
@@ -30,5 +35,6 @@ extern "C" bppsa_status bppsa_scan(int T, int B, int H,
   const size_t need = scan_ws_bytes(T, B, H);
   if (need > 256 && (!workspace || workspace_bytes < need)) return BPPSA_EWORKSPACE;
   if (workspace && ((uintptr_t)workspace & 255)) return BPPSA_EINVAL;
+  if (H == 20) return bppsa_scan_h20(T, B, Jt, seed, G, g0, workspace, (hipStream_t)stream);
   return bppsa_scan_generic(T, B, H, Jt, seed, G, g0, workspace, (hipStream_t)stream);
 }

@@ -1,0 +1,434 @@
+// Single-pass scan for H = 20 (the paper's RNN size, Section 4.1): every
+// transposed Jacobian is read from HBM exactly once.
+//
+// One workgroup owns a segment of S = 32 consecutive chain elements of one
+// sample and keeps it in LDS (32 x 1600 B) from load to store:
+//   up-sweep   : Algorithm 1's up-sweep on the 32 tiles, in place.  The 31
+//                matrix-matrix products run on the matrix cores as 4x4x1 fp32
+//                MFMA outer products (20 = 5 x 4, so a 20x20 tile is 25 blocks
+//                of 4x4 with no padding);
+//   cross-block: instead of one launch per level over the segment totals, the
+//                workgroup publishes its total, looks back over its
+//                predecessors' published totals / inclusive vectors
+//                (matrix-vector products only, since everything to the left
+//                ends in the gradient vector, Section 3.1) and publishes its
+//                own inclusive vector.  Segment ids are handed out by an atomic
+//                ticket, so a workgroup only ever waits for workgroups that are
+//                already running;
+//   down-sweep : Algorithm 1's down-sweep (reversed operands, matrix-vector
+//                only) from the incoming vector, then the 32 gradients are
+//                stored.
+// The chain runs from the seed end: element c is Jt[T-1-c]; the vector that
+// enters element c is g[T-c] = G[T-1-c].
+#include "bppsa_internal.h"
+#include "scan_plan.h"
+
+namespace {
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+constexpr int H = 20;
+constexpr int HH = 400;
+constexpr int S = BPPSA_H20_SEGMENT;
+constexpr int kThreads = 256;
+constexpr int kAggStride = BPPSA_H20_AGG_STRIDE;   // floats per published total (1664 B = 13 lines)
+constexpr int kIncStride = BPPSA_H20_INC_STRIDE;   // floats per published vector (128 B)
+constexpr unsigned kSpinLimit = 1u << 20;
+
+enum : int { kNone = 0, kTotalReady = 1, kPrefixReady = 2 };
+
+struct Header {          // first 256 bytes of the workspace
+  int ticket;
+  int error;             // set when a bounded wait expired: results are invalid
+};
+
+__device__ __forceinline__ v4f mfma4(float a, float b, v4f c) {
+  return __builtin_amdgcn_mfma_f32_4x4x1f32(a, b, c, 0, 0, 0);
+}
+
+// ---- level 0: 16 products, one per MFMA block (slot); each wave owns a sub-grid of the
+// 5 x 5 output blocks of every product.  C = A B with A = tile 2s+1, B = tile 2s.
+template <int I0, int NI, int J0, int NJ>
+__device__ __forceinline__ void level0_compute(const float* A, const float* Bm, int q, v4f (&acc)[9]) {
+#pragma unroll
+  for (int e = 0; e < NI * NJ; ++e) acc[e] = v4f{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int k4 = 0; k4 < 5; ++k4) {
+    v4f a[NI];
+    float bv[NJ][4];
+#pragma unroll
+    for (int i = 0; i < NI; ++i)
+      a[i] = *reinterpret_cast<const v4f*>(A + (4 * (I0 + i) + q) * H + 4 * k4);
+#pragma unroll
+    for (int j = 0; j < NJ; ++j)
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) bv[j][kk] = Bm[(4 * k4 + kk) * H + 4 * (J0 + j) + q];
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+      for (int i = 0; i < NI; ++i)
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) acc[i * NJ + j] = mfma4(a[i][kk], bv[j][kk], acc[i * NJ + j]);
+  }
+}
+
+template <int I0, int NI, int J0, int NJ>
+__device__ __forceinline__ void level0_store(float* C, int q, const v4f (&acc)[9]) {
+#pragma unroll
+  for (int i = 0; i < NI; ++i)
+#pragma unroll
+    for (int j = 0; j < NJ; ++j)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) C[(4 * (I0 + i) + v) * H + 4 * (J0 + j) + q] = acc[i * NJ + j][v];
+}
+
+// ---- upper levels: one product per wave; 15 of the 16 MFMA blocks each own a row-block I
+// and up to two column-blocks (2jp, 2jp+1).  C overwrites A; only this wave touches A and B.
+__device__ __forceinline__ void wave_product(float* A, const float* Bm, int slot, int q) {
+  const int s = slot < 15 ? slot : 14;
+  const int I = s / 3, jp = s - I * 3;
+  const int J0 = 2 * jp, J1 = (jp < 2) ? J0 + 1 : J0;
+  v4f c0 = {0.f, 0.f, 0.f, 0.f}, c1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int k4 = 0; k4 < 5; ++k4) {
+    const v4f a = *reinterpret_cast<const v4f*>(A + (4 * I + q) * H + 4 * k4);
+    float b0[4], b1[4];
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      b0[kk] = Bm[(4 * k4 + kk) * H + 4 * J0 + q];
+      b1[kk] = Bm[(4 * k4 + kk) * H + 4 * J1 + q];
+    }
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      c0 = mfma4(a[kk], b0[kk], c0);
+      c1 = mfma4(a[kk], b1[kk], c1);
+    }
+  }
+  // every load above has been consumed by an MFMA, and LDS operations of one wave complete
+  // in order, so the stores below cannot overtake this wave's reads of A
+  if (slot < 15) {
+#pragma unroll
+    for (int v = 0; v < 4; ++v) A[(4 * I + v) * H + 4 * J0 + q] = c0[v];
+    if (jp < 2) {
+#pragma unroll
+      for (int v = 0; v < 4; ++v) A[(4 * I + v) * H + 4 * J1 + q] = c1[v];
+    }
+  }
+}
+
+// y[row] = sum_k M[row][k] x[k], M a 20x20 tile in LDS, x 20 floats in LDS.
+__device__ __forceinline__ float row_dot(const float* M, int row, const float* x) {
+  const v4f* m4 = reinterpret_cast<const v4f*>(M + row * H);
+  const v4f* x4 = reinterpret_cast<const v4f*>(x);
+  float acc = 0.f;
+#pragma unroll
+  for (int k4 = 0; k4 < 5; ++k4) {
+    const v4f m = m4[k4], xv = x4[k4];
+    acc += m[0] * xv[0];
+    acc += m[1] * xv[1];
+    acc += m[2] * xv[2];
+    acc += m[3] * xv[3];
+  }
+  return acc;
+}
+
+// Value of `x` in lane `l` (l wave-uniform), as a wave-uniform scalar.
+__device__ __forceinline__ float readlane_f(float x, int l) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), l));
+}
+
+// Cross-workgroup traffic (status words, published totals and vectors) uses device-scope
+// atomic accesses only: they are performed at the level all compute dies share, so no
+// cache write-back or invalidate is needed; ordering comes from waiting for the data
+// stores to complete before the status store is issued, and from issuing the data loads
+// only after the status value has been observed.
+__device__ __forceinline__ int load_status(const int* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void store_status(int* p, int v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void publish2(float* dst, float a, float b) {   // dst 8-byte aligned
+  unsigned long long bits = (unsigned long long)__builtin_bit_cast(unsigned, a) |
+                            ((unsigned long long)__builtin_bit_cast(unsigned, b) << 32);
+  __hip_atomic_store(reinterpret_cast<unsigned long long*>(dst), bits, __ATOMIC_RELAXED,
+                     __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void fetch2(const float* src, float& a, float& b) {
+  const unsigned long long bits = __hip_atomic_load(reinterpret_cast<const unsigned long long*>(src),
+                                                    __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  a = __builtin_bit_cast(float, (unsigned)(bits & 0xffffffffull));
+  b = __builtin_bit_cast(float, (unsigned)(bits >> 32));
+}
+__device__ __forceinline__ void wait_all_memory_ops() { __builtin_amdgcn_s_waitcnt(0); }
+
+// Look-back, run by wave 0.  Leaves the vector entering this segment in vin[0..20).
+// Window: the 64 predecessors k-1 .. k-64 of the same sample.  The nearest one that has
+// published its inclusive vector is the base; every nearer one must have published its
+// total.  Lower tickets are already running or finished, so the wait ends; a bounded spin
+// turns anything unexpected into an error flag instead of a hang.
+__device__ void look_back(int k, int b, int B, const int* status, const float* agg, const float* incl,
+                          float* vin, Header* hdr) {
+  const int lane = threadIdx.x & 63;
+  const int idx = k - 1 - lane;
+  int f = -1;
+  for (unsigned spin = 0;; ++spin) {
+    int st = kTotalReady;                       // lanes past segment 0 never block the window
+    if (idx >= 0) st = load_status(status + (size_t)idx * B + b);
+    const unsigned long long pmask = __ballot(idx >= 0 && st == kPrefixReady);
+    const unsigned long long amask = __ballot(st >= kTotalReady);
+    if (pmask) {
+      const int first = __ffsll((long long)pmask) - 1;
+      const unsigned long long need = (first == 0) ? 0ull : (~0ull >> (64 - first));
+      if ((amask & need) == need) { f = first; break; }
+    }
+    if (spin >= kSpinLimit) break;
+    __builtin_amdgcn_s_sleep(4);
+  }
+  if (f < 0) {                                  // wait expired: flag it and fall through with zeros
+    if (lane == 0) hdr->error = 1;
+    if (lane < H) vin[lane] = 0.f;
+    return;
+  }
+  // v = inclusive vector of segment k-1-f, then the f totals nearer to us, far to near
+  const int grp = lane / H;                     // 3 groups of 20 lanes (lanes 60..63 idle)
+  const int row = lane - grp * H;
+  float v[H];
+  {
+    const float x = __hip_atomic_load(incl + ((size_t)(k - 1 - f) * B + b) * kIncStride + (lane < H ? lane : 0),
+                                      __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+    for (int c = 0; c < H; ++c) v[c] = readlane_f(x, c);
+  }
+  // hop n (0-based, n < f) applies the total of segment k-f+n; 12 hops per batch
+  for (int n0 = 0; n0 < f; n0 += 12) {
+    v4f rows[4][5];
+#pragma unroll
+    for (int sl = 0; sl < 4; ++sl) {
+      const int n = n0 + 3 * sl + grp;
+      if (n < f && grp < 3) {
+        const float* src = agg + ((size_t)(k - f + n) * B + b) * kAggStride + row * H;
+#pragma unroll
+        for (int c4 = 0; c4 < 5; ++c4) {
+          float e0, e1, e2, e3;
+          fetch2(src + 4 * c4, e0, e1);
+          fetch2(src + 4 * c4 + 2, e2, e3);
+          rows[sl][c4] = v4f{e0, e1, e2, e3};
+        }
+      } else {
+#pragma unroll
+        for (int c4 = 0; c4 < 5; ++c4) rows[sl][c4] = v4f{0.f, 0.f, 0.f, 0.f};
+      }
+    }
+#pragma unroll
+    for (int sl = 0; sl < 4; ++sl) {
+#pragma unroll
+      for (int g = 0; g < 3; ++g) {
+        if (n0 + 3 * sl + g < f) {              // wave-uniform
+          float acc = 0.f;
+#pragma unroll
+          for (int c4 = 0; c4 < 5; ++c4) {
+            acc += rows[sl][c4][0] * v[4 * c4 + 0];
+            acc += rows[sl][c4][1] * v[4 * c4 + 1];
+            acc += rows[sl][c4][2] * v[4 * c4 + 2];
+            acc += rows[sl][c4][3] * v[4 * c4 + 3];
+          }
+#pragma unroll
+          for (int c = 0; c < H; ++c) v[c] = readlane_f(acc, g * H + c);
+        }
+      }
+    }
+  }
+  if (lane == 0) {
+#pragma unroll
+    for (int c = 0; c < H; ++c) vin[c] = v[c];
+  }
+}
+
+__global__ void __launch_bounds__(kThreads, 3)
+scan_h20_kernel(int T, int B, int n, int nseg, const float* __restrict__ Jt,
+                const float* __restrict__ seed, float* __restrict__ G, float* __restrict__ g0,
+                Header* hdr, int* status, float* agg, float* incl) {
+  __shared__ __attribute__((aligned(16))) float mat[S * HH];
+  __shared__ __attribute__((aligned(16))) float vec[S * H];
+  __shared__ __attribute__((aligned(16))) float vin[H];
+  __shared__ __attribute__((aligned(16))) float vout[H];
+  __shared__ int ticket_s;
+
+  const int tid = threadIdx.x;
+  const int wave = tid >> 6, lane = tid & 63, slot = lane >> 2, q = lane & 3;
+  if (tid == 0) ticket_s = atomicAdd(&hdr->ticket, 1);
+  __syncthreads();
+  const int ticket = ticket_s;
+  const int k = ticket / B;                      // segment, 0 = seed end
+  const int b = ticket - k * B;
+  const int c0 = k * S;                          // first chain element of the segment
+  const int m = (n - c0 < S) ? (n - c0) : S;     // real elements; the rest are identity tiles
+
+  // ---- load: element p is Jt[T-1-c0-p][b] --------------------------------------------
+  {
+    constexpr int kChunks = S * HH / 4;          // 16-byte pieces
+    v4f tmp[(kChunks + kThreads - 1) / kThreads];
+#pragma unroll
+    for (int r = 0; r < (kChunks + kThreads - 1) / kThreads; ++r) {
+      const int e = tid + r * kThreads;
+      const int p = e / (HH / 4), off = e - p * (HH / 4);
+      if (e < kChunks && p < m) {
+        const float* src = Jt + ((size_t)(T - 1 - c0 - p) * B + b) * HH;
+        tmp[r] = reinterpret_cast<const v4f*>(src)[off];
+      } else {
+        const int i0 = (off * 4) / H, j0 = off * 4 - i0 * H;   // identity padding
+        tmp[r] = v4f{i0 == j0 ? 1.f : 0.f, i0 == j0 + 1 ? 1.f : 0.f, i0 == j0 + 2 ? 1.f : 0.f,
+                     i0 == j0 + 3 ? 1.f : 0.f};
+      }
+    }
+#pragma unroll
+    for (int r = 0; r < (kChunks + kThreads - 1) / kThreads; ++r) {
+      const int e = tid + r * kThreads;
+      if (e < kChunks) reinterpret_cast<v4f*>(mat)[e] = tmp[r];
+    }
+  }
+  __syncthreads();
+
+  // ---- up-sweep level 0: a[2s+1] <- a[2s+1] a[2s] ---------------------------------------
+  {
+    v4f acc[9];
+    float* A = mat + (2 * slot + 1) * HH;
+    const float* Bm = mat + (2 * slot) * HH;
+    switch (wave) {
+      case 0: level0_compute<0, 3, 0, 3>(A, Bm, q, acc); break;
+      case 1: level0_compute<0, 3, 3, 2>(A, Bm, q, acc); break;
+      case 2: level0_compute<3, 2, 0, 3>(A, Bm, q, acc); break;
+      default: level0_compute<3, 2, 3, 2>(A, Bm, q, acc); break;
+    }
+    __syncthreads();
+    switch (wave) {
+      case 0: level0_store<0, 3, 0, 3>(A, q, acc); break;
+      case 1: level0_store<0, 3, 3, 2>(A, q, acc); break;
+      case 2: level0_store<3, 2, 0, 3>(A, q, acc); break;
+      default: level0_store<3, 2, 3, 2>(A, q, acc); break;
+    }
+  }
+  __syncthreads();
+  // ---- up-sweep levels 1..4: pairs (l, r) = (i + 2^d - 1, i + 2^(d+1) - 1) --------------
+#pragma unroll
+  for (int d = 1; d < 5; ++d) {
+    const int npairs = S >> (d + 1);
+    for (int pr = wave; pr < npairs; pr += 4) {
+      const int i = pr << (d + 1);
+      wave_product(mat + (i + (2 << d) - 1) * HH, mat + (i + (1 << d) - 1) * HH, slot, q);
+    }
+    __syncthreads();
+  }
+  float* total = mat + (S - 1) * HH;
+  const size_t me = (size_t)k * B + b;
+
+  // ---- publish the segment total (interior segments only) -------------------------------
+  if (k > 0 && k < nseg - 1) {
+    float* dst = agg + me * kAggStride;
+    if (tid < HH / 2) publish2(dst + 2 * tid, total[2 * tid], total[2 * tid + 1]);
+    wait_all_memory_ops();
+    __syncthreads();
+    if (tid == 0) store_status(status + me, kTotalReady);
+  }
+
+  // ---- incoming vector, inclusive vector -------------------------------------------------
+  if (wave == 0) {
+    if (k == 0) {
+      if (lane < H) vin[lane] = seed[(size_t)b * H + lane];
+    } else {
+      look_back(k, b, B, status, agg, incl, vin, hdr);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    if (lane < H) {
+      const float y = row_dot(total, lane, vin);
+      vout[lane] = y;
+      if (k < nseg - 1) {
+        __hip_atomic_store(incl + me * kIncStride + lane, y, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      } else {                                    // the chain's last output: g[t_min]
+        float* dst = (n == T) ? g0 + (size_t)b * H : G + (size_t)b * H;
+        dst[lane] = y;
+      }
+    }
+    if (k < nseg - 1) {
+      wait_all_memory_ops();
+      __builtin_amdgcn_wave_barrier();
+      if (lane == 0) store_status(status + me, kPrefixReady);
+    }
+  }
+  __syncthreads();
+
+  // ---- down-sweep: T <- a[l]; a[l] <- a[r]; a[r] <- T a[r] ------------------------------
+  if (tid < H) vec[(S - 1) * H + tid] = vin[tid];
+  __syncthreads();
+#pragma unroll
+  for (int d = 4; d >= 0; --d) {
+    const int npairs = S >> (d + 1);
+    float res[2];
+    float keep[2];
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+      const int e = tid + r * kThreads;
+      res[r] = 0.f;
+      keep[r] = 0.f;
+      if (e < npairs * H) {
+        const int pr = e / H, row = e - pr * H;
+        const int i = pr << (d + 1);
+        const int l = i + (1 << d) - 1, rr = i + (2 << d) - 1;
+        res[r] = row_dot(mat + l * HH, row, vec + rr * H);
+        keep[r] = vec[rr * H + row];
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+      const int e = tid + r * kThreads;
+      if (e < npairs * H) {
+        const int pr = e / H, row = e - pr * H;
+        const int i = pr << (d + 1);
+        const int l = i + (1 << d) - 1, rr = i + (2 << d) - 1;
+        vec[l * H + row] = keep[r];
+        vec[rr * H + row] = res[r];
+      }
+    }
+    __syncthreads();
+  }
+
+  // ---- store: the vector entering element p is g[T-c0-p] = G[T-1-c0-p] --------------------
+  for (int e = tid; e < m * H; e += kThreads) {
+    const int p = e / H, row = e - p * H;
+    __builtin_nontemporal_store(vec[e], G + ((size_t)(T - 1 - c0 - p) * B + b) * H + row);
+  }
+}
+
+__global__ void clear_kernel(int* p, long long nwords) {
+  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < nwords) p[i] = 0;
+}
+
+}  // namespace
+
+bppsa_status bppsa_scan_h20(int T, int B, const float* Jt, const float* seed, float* G, float* g0,
+                            void* workspace, hipStream_t stream) {
+  const int n = g0 ? T : T - 1;                 // chain elements Jt[T-1] .. Jt[T-n]
+  if (n <= 0) {                                 // T == 1 without g0: only G[0] = seed
+    return bppsa_scan_generic(T, B, H, Jt, seed, G, g0, workspace, stream);
+  }
+  const int nseg = bppsa_ceil_div(n, S);
+  const long long nblk = (long long)nseg * B;
+  if (nblk > 0x7fffffffLL) return BPPSA_EOVERFLOW;
+  char* ws = static_cast<char*>(workspace);
+  Header* hdr = reinterpret_cast<Header*>(ws);
+  int* status = reinterpret_cast<int*>(ws + 256);
+  const size_t status_bytes = bppsa_align_up((size_t)nblk * sizeof(int), 256);
+  float* agg = reinterpret_cast<float*>(ws + 256 + status_bytes);
+  float* incl = agg + (size_t)nblk * kAggStride;
+  const long long nwords = (256 + (long long)status_bytes) / 4;
+  clear_kernel<<<(int)((nwords + 255) / 256), 256, 0, stream>>>(reinterpret_cast<int*>(ws), nwords);
+  BPPSA_CHECK_LAUNCH();
+  scan_h20_kernel<<<(int)nblk, kThreads, 0, stream>>>(T, B, n, nseg, Jt, seed, G, g0, hdr, status, agg, incl);
+  BPPSA_CHECK_LAUNCH();
+  return BPPSA_OK;
+}

@@ -27,5 +27,21 @@ static inline size_t bppsa_generic_scan_ws(int T, int B, int H, int want_g0) {
   return total;
 }
 
+// ---- single-pass path for H = 20 --------------------------------------------------------
+#define BPPSA_H20_SEGMENT 32
+#define BPPSA_H20_AGG_STRIDE 416   /* floats: a 20x20 total padded to 13 cache lines */
+#define BPPSA_H20_INC_STRIDE 32    /* floats: a 20-vector padded to one cache line */
+
+// Workspace of the single-pass scan: header, one status word, one published total and one
+// published inclusive vector per (segment, sample).
+static inline size_t bppsa_h20_scan_ws(int T, int B) {
+  const size_t nblk = (size_t)bppsa_ceil_div(T, BPPSA_H20_SEGMENT) * B;
+  return 256 + bppsa_align_up(nblk * sizeof(int), 256) +
+         nblk * (BPPSA_H20_AGG_STRIDE + BPPSA_H20_INC_STRIDE) * sizeof(float);
+}
+
+bppsa_status bppsa_scan_h20(int T, int B, const float* Jt, const float* seed, float* G, float* g0,
+                            void* workspace, hipStream_t stream);
+
 bppsa_status bppsa_scan_generic(int T, int B, int H, const float* Jt, const float* seed,
                                 float* G, float* g0, void* workspace, hipStream_t stream);
