@@ -29,6 +29,8 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 
 constexpr int H = 20;
 constexpr int HH = 400;
+constexpr int TS = 404;                 // LDS tile stride in floats: 400 plus one 16-byte pad, so that
+                                        // tiles two apart do not start on the same LDS bank
 constexpr int S = BPPSA_H20_SEGMENT;
 constexpr int kThreads = 256;
 constexpr int kAggStride = BPPSA_H20_AGG_STRIDE;   // floats per published total (1664 B = 13 lines)
@@ -37,10 +39,22 @@ constexpr unsigned kSpinLimit = 1u << 20;
 
 enum : int { kNone = 0, kTotalReady = 1, kPrefixReady = 2 };
 
-struct Header {          // first 256 bytes of the workspace
-  int ticket;
+#ifdef BPPSA_TRACE
+__device__ long long* g_trace;
+#define BPPSA_LB_TRACE(slot, val) do { if (g_trace && (threadIdx.x & 63) == 0) g_trace[((size_t)k * B + b) * 16 + (slot)] = (val); } while (0)
+#else
+#define BPPSA_LB_TRACE(slot, val) do { } while (0)
+#endif
+
+constexpr int kMaxQueues = 8;     // one work queue per compute die (XCD)
+constexpr int kHeaderBytes = BPPSA_H20_HEADER_BYTES;
+
+struct Header {          // first kHeaderBytes of the workspace, zeroed before every scan
   int error;             // set when a bounded wait expired: results are invalid
+  int pad[31];
+  int ticket[kMaxQueues][32];   // next segment of each queue, one cache line apart
 };
+static_assert(sizeof(Header) <= kHeaderBytes, "header does not fit");
 
 __device__ __forceinline__ v4f mfma4(float a, float b, v4f c) {
   return __builtin_amdgcn_mfma_f32_4x4x1f32(a, b, c, 0, 0, 0);
@@ -52,23 +66,32 @@ template <int I0, int NI, int J0, int NJ>
 __device__ __forceinline__ void level0_compute(const float* A, const float* Bm, int q, v4f (&acc)[9]) {
 #pragma unroll
   for (int e = 0; e < NI * NJ; ++e) acc[e] = v4f{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-  for (int k4 = 0; k4 < 5; ++k4) {
-    v4f a[NI];
-    float bv[NJ][4];
+  // operands of step k4 + 1 are requested from LDS before the MFMAs of step k4 are issued
+  v4f a[2][NI];
+  float bv[2][NJ][4];
+  auto fetch = [&](int buf, int k4) {
 #pragma unroll
     for (int i = 0; i < NI; ++i)
-      a[i] = *reinterpret_cast<const v4f*>(A + (4 * (I0 + i) + q) * H + 4 * k4);
+      a[buf][i] = *reinterpret_cast<const v4f*>(A + (4 * (I0 + i) + q) * H + 4 * k4);
 #pragma unroll
     for (int j = 0; j < NJ; ++j)
 #pragma unroll
-      for (int kk = 0; kk < 4; ++kk) bv[j][kk] = Bm[(4 * k4 + kk) * H + 4 * (J0 + j) + q];
+      for (int kk = 0; kk < 4; ++kk) bv[buf][j][kk] = Bm[(4 * k4 + kk) * H + 4 * (J0 + j) + q];
+  };
+  fetch(0, 0);
+#pragma unroll
+  for (int k4 = 0; k4 < 5; ++k4) {
+    const int cur = k4 & 1;
+    if (k4 < 4) fetch(cur ^ 1, k4 + 1);
+    __builtin_amdgcn_sched_barrier(0);     // keep the prefetch ahead of this step's MFMAs
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk)
 #pragma unroll
       for (int i = 0; i < NI; ++i)
 #pragma unroll
-        for (int j = 0; j < NJ; ++j) acc[i * NJ + j] = mfma4(a[i][kk], bv[j][kk], acc[i * NJ + j]);
+        for (int j = 0; j < NJ; ++j)
+          acc[i * NJ + j] = mfma4(a[cur][i][kk], bv[cur][j][kk], acc[i * NJ + j]);
+    __builtin_amdgcn_sched_barrier(0);
   }
 }
 
@@ -89,19 +112,25 @@ __device__ __forceinline__ void wave_product(float* A, const float* Bm, int slot
   const int I = s / 3, jp = s - I * 3;
   const int J0 = 2 * jp, J1 = (jp < 2) ? J0 + 1 : J0;
   v4f c0 = {0.f, 0.f, 0.f, 0.f}, c1 = {0.f, 0.f, 0.f, 0.f};
+  // all 45 operand loads are issued up front (60 registers), then the 40 MFMAs run back to back
+  v4f a[5];
+  float b0[5][4], b1[5][4];
 #pragma unroll
   for (int k4 = 0; k4 < 5; ++k4) {
-    const v4f a = *reinterpret_cast<const v4f*>(A + (4 * I + q) * H + 4 * k4);
-    float b0[4], b1[4];
+    a[k4] = *reinterpret_cast<const v4f*>(A + (4 * I + q) * H + 4 * k4);
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
-      b0[kk] = Bm[(4 * k4 + kk) * H + 4 * J0 + q];
-      b1[kk] = Bm[(4 * k4 + kk) * H + 4 * J1 + q];
+      b0[k4][kk] = Bm[(4 * k4 + kk) * H + 4 * J0 + q];
+      b1[k4][kk] = Bm[(4 * k4 + kk) * H + 4 * J1 + q];
     }
+  }
+  __builtin_amdgcn_sched_barrier(0);       // do not sink the loads between the MFMAs
+#pragma unroll
+  for (int k4 = 0; k4 < 5; ++k4) {
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
-      c0 = mfma4(a[kk], b0[kk], c0);
-      c1 = mfma4(a[kk], b1[kk], c1);
+      c0 = mfma4(a[k4][kk], b0[k4][kk], c0);
+      c1 = mfma4(a[k4][kk], b1[k4][kk], c1);
     }
   }
   // every load above has been consumed by an MFMA, and LDS operations of one wave complete
@@ -137,26 +166,46 @@ __device__ __forceinline__ float readlane_f(float x, int l) {
   return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), l));
 }
 
-// Cross-workgroup traffic (status words, published totals and vectors) uses device-scope
-// atomic accesses only: they are performed at the level all compute dies share, so no
-// cache write-back or invalidate is needed; ordering comes from waiting for the data
-// stores to complete before the status store is issued, and from issuing the data loads
-// only after the status value has been observed.
-__device__ __forceinline__ int load_status(const int* p) {
-  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+// Cross-workgroup traffic (status words, published totals and vectors) uses relaxed atomic
+// accesses only, so no cache write-back or invalidate is ever issued; ordering comes from
+// waiting for the data stores to complete before the status store is issued, and from
+// issuing the data loads only after the status value has been observed.
+// SCOPE is the level at which those accesses are performed:
+//   agent     - the memory side shared by all compute dies (works for any placement);
+//   workgroup - the L2 of the compute die the wave runs on.  The vector L1 is
+//               write-through and these accesses miss it, so they are coherent between all
+//               workgroups of ONE die; the kernel uses this only for chains whose segments
+//               all run on the same die (see the queue selection below).
+// A die-local status read is an atomic add of a run-time zero: read-modify-write atomics are
+// always performed in the L2, whereas a workgroup-scope load may be served by the L1 of the
+// compute unit and would then never see another unit's update.
+template <int SCOPE>
+__device__ __forceinline__ int load_status(int* p, int zero) {
+  if (SCOPE == __HIP_MEMORY_SCOPE_WORKGROUP) return __hip_atomic_fetch_add(p, zero, __ATOMIC_RELAXED, SCOPE);
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, SCOPE);
 }
+template <int SCOPE>
 __device__ __forceinline__ void store_status(int* p, int v) {
-  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, SCOPE);
 }
+template <int SCOPE>
+__device__ __forceinline__ void publish1(float* dst, float a) {
+  __hip_atomic_store(dst, a, __ATOMIC_RELAXED, SCOPE);
+}
+template <int SCOPE>
+__device__ __forceinline__ float fetch1(const float* src) {
+  return __hip_atomic_load(src, __ATOMIC_RELAXED, SCOPE);
+}
+template <int SCOPE>
 __device__ __forceinline__ void publish2(float* dst, float a, float b) {   // dst 8-byte aligned
   unsigned long long bits = (unsigned long long)__builtin_bit_cast(unsigned, a) |
                             ((unsigned long long)__builtin_bit_cast(unsigned, b) << 32);
-  __hip_atomic_store(reinterpret_cast<unsigned long long*>(dst), bits, __ATOMIC_RELAXED,
-                     __HIP_MEMORY_SCOPE_AGENT);
+  __hip_atomic_store(reinterpret_cast<unsigned long long*>(dst), bits, __ATOMIC_RELAXED, SCOPE);
 }
+template <int SCOPE>
 __device__ __forceinline__ void fetch2(const float* src, float& a, float& b) {
-  const unsigned long long bits = __hip_atomic_load(reinterpret_cast<const unsigned long long*>(src),
-                                                    __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  const unsigned long long bits =
+      __hip_atomic_load(reinterpret_cast<const unsigned long long*>(src), __ATOMIC_RELAXED, SCOPE);
   a = __builtin_bit_cast(float, (unsigned)(bits & 0xffffffffull));
   b = __builtin_bit_cast(float, (unsigned)(bits >> 32));
 }
@@ -167,14 +216,15 @@ __device__ __forceinline__ void wait_all_memory_ops() { __builtin_amdgcn_s_waitc
 // published its inclusive vector is the base; every nearer one must have published its
 // total.  Lower tickets are already running or finished, so the wait ends; a bounded spin
 // turns anything unexpected into an error flag instead of a hang.
-__device__ void look_back(int k, int b, int B, const int* status, const float* agg, const float* incl,
+template <int SCOPE>
+__device__ void look_back(int k, int b, int B, int zero, int* status, const float* agg, const float* incl,
                           float* vin, Header* hdr) {
   const int lane = threadIdx.x & 63;
   const int idx = k - 1 - lane;
   int f = -1;
   for (unsigned spin = 0;; ++spin) {
     int st = kTotalReady;                       // lanes past segment 0 never block the window
-    if (idx >= 0) st = load_status(status + (size_t)idx * B + b);
+    if (idx >= 0) st = load_status<SCOPE>(status + (size_t)idx * B + b, zero);
     const unsigned long long pmask = __ballot(idx >= 0 && st == kPrefixReady);
     const unsigned long long amask = __ballot(st >= kTotalReady);
     if (pmask) {
@@ -182,230 +232,311 @@ __device__ void look_back(int k, int b, int B, const int* status, const float* a
       const unsigned long long need = (first == 0) ? 0ull : (~0ull >> (64 - first));
       if ((amask & need) == need) { f = first; break; }
     }
+    // give up when the wait is hopeless, or as soon as any other workgroup has given up
     if (spin >= kSpinLimit) break;
-    __builtin_amdgcn_s_sleep(4);
+    if ((spin & 63) == 63 && __hip_atomic_load(&hdr->error, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) break;
+    __builtin_amdgcn_s_sleep(2);
   }
-  if (f < 0) {                                  // wait expired: flag it and fall through with zeros
-    if (lane == 0) hdr->error = 1;
+  if (f < 0) {                                  // flag it and fall through with zeros
+    if (lane == 0) __hip_atomic_store(&hdr->error, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (lane < H) vin[lane] = 0.f;
     return;
   }
+  BPPSA_LB_TRACE(8, wall_clock64());
+  BPPSA_LB_TRACE(9, (long long)f);
   // v = inclusive vector of segment k-1-f, then the f totals nearer to us, far to near
-  const int grp = lane / H;                     // 3 groups of 20 lanes (lanes 60..63 idle)
-  const int row = lane - grp * H;
-  float v[H];
-  {
-    const float x = __hip_atomic_load(incl + ((size_t)(k - 1 - f) * B + b) * kIncStride + (lane < H ? lane : 0),
-                                      __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __builtin_amdgcn_s_setprio(3);                // the chain of hops outranks the MFMA waves
+  // Three groups of 20 lanes each own one row of a published total (lanes 60..63 mirror
+  // group 2).  Totals are fetched six at a time into two register buffers; every load is
+  // unconditional (indices past the end are clamped), so the buffers stream while earlier
+  // hops are being applied and the whole chain costs about one L2 round trip plus the hops.
+  const int grp = lane < 3 * H ? lane / H : 2;
+  const int row = lane < 3 * H ? lane - grp * H : lane - 44;
+  auto fetch_batch = [&](v4f (&buf)[2][5], int n0) {
 #pragma unroll
-    for (int c = 0; c < H; ++c) v[c] = readlane_f(x, c);
-  }
-  // hop n (0-based, n < f) applies the total of segment k-f+n; 12 hops per batch
-  for (int n0 = 0; n0 < f; n0 += 12) {
-    v4f rows[4][5];
+    for (int sl = 0; sl < 2; ++sl) {
+      int n = n0 + 3 * sl + grp;
+      n = n < f ? n : f - 1;
+      n = n < 0 ? 0 : n;
+      const float* src = agg + ((size_t)(k - f + n) * B + b) * kAggStride + row * H;
 #pragma unroll
-    for (int sl = 0; sl < 4; ++sl) {
-      const int n = n0 + 3 * sl + grp;
-      if (n < f && grp < 3) {
-        const float* src = agg + ((size_t)(k - f + n) * B + b) * kAggStride + row * H;
-#pragma unroll
-        for (int c4 = 0; c4 < 5; ++c4) {
-          float e0, e1, e2, e3;
-          fetch2(src + 4 * c4, e0, e1);
-          fetch2(src + 4 * c4 + 2, e2, e3);
-          rows[sl][c4] = v4f{e0, e1, e2, e3};
-        }
-      } else {
-#pragma unroll
-        for (int c4 = 0; c4 < 5; ++c4) rows[sl][c4] = v4f{0.f, 0.f, 0.f, 0.f};
+      for (int c4 = 0; c4 < 5; ++c4) {
+        float e0, e1, e2, e3;
+        fetch2<SCOPE>(src + 4 * c4, e0, e1);
+        fetch2<SCOPE>(src + 4 * c4 + 2, e2, e3);
+        buf[sl][c4] = v4f{e0, e1, e2, e3};
       }
     }
+  };
+  float v[H];
+  auto apply_batch = [&](const v4f (&buf)[2][5], int n0) {
 #pragma unroll
-    for (int sl = 0; sl < 4; ++sl) {
+    for (int sl = 0; sl < 2; ++sl) {
 #pragma unroll
       for (int g = 0; g < 3; ++g) {
         if (n0 + 3 * sl + g < f) {              // wave-uniform
-          float acc = 0.f;
+          // four independent partial sums: the hop is on the critical path of every
+          // later segment of this sample, so keep its dependency chain short
+          float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
 #pragma unroll
           for (int c4 = 0; c4 < 5; ++c4) {
-            acc += rows[sl][c4][0] * v[4 * c4 + 0];
-            acc += rows[sl][c4][1] * v[4 * c4 + 1];
-            acc += rows[sl][c4][2] * v[4 * c4 + 2];
-            acc += rows[sl][c4][3] * v[4 * c4 + 3];
+            a0 += buf[sl][c4][0] * v[4 * c4 + 0];
+            a1 += buf[sl][c4][1] * v[4 * c4 + 1];
+            a2 += buf[sl][c4][2] * v[4 * c4 + 2];
+            a3 += buf[sl][c4][3] * v[4 * c4 + 3];
           }
+          const float acc = (a0 + a1) + (a2 + a3);
 #pragma unroll
           for (int c = 0; c < H; ++c) v[c] = readlane_f(acc, g * H + c);
         }
       }
     }
+  };
+  const float x = fetch1<SCOPE>(incl + ((size_t)(k - 1 - f) * B + b) * kIncStride + (lane < H ? lane : 0));
+  v4f buf0[2][5], buf1[2][5];
+  if (f > 0) {                                  // wave-uniform; with f == 0 no total is needed
+    fetch_batch(buf0, 0);
+    fetch_batch(buf1, 6);
+  }
+#pragma unroll
+  for (int c = 0; c < H; ++c) v[c] = readlane_f(x, c);
+  // hop n (0-based, n < f) applies the total of segment k-f+n
+  for (int n0 = 0; n0 < f; n0 += 12) {
+    apply_batch(buf0, n0);
+    if (n0 + 12 < f) fetch_batch(buf0, n0 + 12);
+    apply_batch(buf1, n0 + 6);
+    if (n0 + 18 < f) fetch_batch(buf1, n0 + 18);
   }
   if (lane == 0) {
 #pragma unroll
     for (int c = 0; c < H; ++c) vin[c] = v[c];
   }
+  BPPSA_LB_TRACE(10, wall_clock64());
+  __builtin_amdgcn_s_setprio(0);
 }
 
+#ifdef BPPSA_TRACE
+#define BPPSA_STAMP(i) do { if (trace && threadIdx.x == 0) trace[(size_t)me * 16 + (i)] = wall_clock64(); } while (0)
+#define BPPSA_TRACE_PARAM , long long* trace
+#define BPPSA_TRACE_ARG , nullptr
+#else
+#define BPPSA_STAMP(i) do { } while (0)
+#define BPPSA_TRACE_PARAM
+#define BPPSA_TRACE_ARG
+#endif
+
+// Identity of the compute die (XCD) this wave runs on: bits [3:0] of hardware register
+// XCC_ID (id 20).
+__device__ __forceinline__ int xcc_id() { return __builtin_amdgcn_s_getreg((3 << 11) | 20) & 15; }
+
+// Work distribution.  The samples are dealt round-robin to `nq` queues (sample b belongs to
+// queue b % nq); a queue hands out its (segment, sample) pairs in chain order through an
+// atomic ticket.  Workgroups are persistent: each drains one queue and exits when it is
+// empty, so a workgroup only ever waits for tickets that were taken before its own.
+//   LOCAL  - nq = 8 and the queue is chosen by the die the workgroup runs on: every chain
+//            then lives on one die and its look-back traffic stays in that die's L2.
+//   !LOCAL - the queue is blockIdx % nq and all cross-workgroup traffic is device scope.
+//            This form is correct for any placement; it serves batch sizes that are not a
+//            multiple of 8 and, launched after the LOCAL form, picks up whatever a die
+//            that received no workgroups has left behind (normally nothing).
+template <bool LOCAL>
 __global__ void __launch_bounds__(kThreads, 3)
-scan_h20_kernel(int T, int B, int n, int nseg, const float* __restrict__ Jt,
+scan_h20_kernel(int T, int B, int n, int nseg, int nq, int zero, const float* __restrict__ Jt,
                 const float* __restrict__ seed, float* __restrict__ G, float* __restrict__ g0,
-                Header* hdr, int* status, float* agg, float* incl) {
-  __shared__ __attribute__((aligned(16))) float mat[S * HH];
-  __shared__ __attribute__((aligned(16))) float vec[S * H];
+                Header* hdr, int* status, float* agg, float* incl BPPSA_TRACE_PARAM) {
+  constexpr int SCOPE = LOCAL ? __HIP_MEMORY_SCOPE_WORKGROUP : __HIP_MEMORY_SCOPE_AGENT;
+  // 32 tiles, then room so that the 32 down-sweep vectors can start on top of the last tile
+  // (the segment total, dead once the inclusive vector has been formed)
+  __shared__ __attribute__((aligned(16))) float lds[(S - 1) * TS + S * H];
   __shared__ __attribute__((aligned(16))) float vin[H];
-  __shared__ __attribute__((aligned(16))) float vout[H];
   __shared__ int ticket_s;
+  float* mat = lds;
+  float* vec = lds + (S - 1) * TS;
 
-  const int tid = threadIdx.x;
-  const int wave = tid >> 6, lane = tid & 63, slot = lane >> 2, q = lane & 3;
-  if (tid == 0) ticket_s = atomicAdd(&hdr->ticket, 1);
-  __syncthreads();
-  const int ticket = ticket_s;
-  const int k = ticket / B;                      // segment, 0 = seed end
-  const int b = ticket - k * B;
-  const int c0 = k * S;                          // first chain element of the segment
-  const int m = (n - c0 < S) ? (n - c0) : S;     // real elements; the rest are identity tiles
+  const int qid = LOCAL ? (xcc_id() & (kMaxQueues - 1)) : (int)(blockIdx.x % (unsigned)nq);
+  if (qid >= nq) return;
+  const int bq = (B - qid + nq - 1) / nq;        // samples of this queue: qid, qid + nq, ...
+  const int quota = nseg * bq;
 
-  // ---- load: element p is Jt[T-1-c0-p][b] --------------------------------------------
-  {
-    constexpr int kChunks = S * HH / 4;          // 16-byte pieces
-    v4f tmp[(kChunks + kThreads - 1) / kThreads];
+  for (;;) {
+    // Re-derive the lane coordinates inside the loop from an opaque copy of the thread id:
+    // otherwise every LDS address of the body is hoisted out of the loop and the hoisted
+    // values spill.
+    int tid = threadIdx.x;
+    asm volatile("" : "+v"(tid));
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, slot = lane >> 2, q = lane & 3;
+    if (tid == 0) ticket_s = __hip_atomic_fetch_add(&hdr->ticket[qid][0], 1, __ATOMIC_RELAXED, SCOPE);
+    __syncthreads();
+    const int ticket = ticket_s;
+    if (ticket >= quota) break;                  // uniform: the queue is empty
+    const int k = ticket / bq;                   // segment, 0 = seed end
+    const int b = qid + nq * (ticket - k * bq);
+    const size_t me = (size_t)k * B + b;
+    BPPSA_STAMP(0);
+    const int c0 = k * S;                        // first chain element of the segment
+    const int m = (n - c0 < S) ? (n - c0) : S;   // real elements; the rest are identity tiles
+
+    // ---- load: element p is Jt[T-1-c0-p][b] ------------------------------------------
+    {
+      constexpr int kChunks = S * HH / 4;        // 16-byte pieces
+      v4f tmp[(kChunks + kThreads - 1) / kThreads];
 #pragma unroll
-    for (int r = 0; r < (kChunks + kThreads - 1) / kThreads; ++r) {
-      const int e = tid + r * kThreads;
-      const int p = e / (HH / 4), off = e - p * (HH / 4);
-      if (e < kChunks && p < m) {
-        const float* src = Jt + ((size_t)(T - 1 - c0 - p) * B + b) * HH;
-        tmp[r] = reinterpret_cast<const v4f*>(src)[off];
-      } else {
-        const int i0 = (off * 4) / H, j0 = off * 4 - i0 * H;   // identity padding
-        tmp[r] = v4f{i0 == j0 ? 1.f : 0.f, i0 == j0 + 1 ? 1.f : 0.f, i0 == j0 + 2 ? 1.f : 0.f,
-                     i0 == j0 + 3 ? 1.f : 0.f};
+      for (int r = 0; r < (kChunks + kThreads - 1) / kThreads; ++r) {
+        const int e = tid + r * kThreads;
+        const int p = e / (HH / 4), off = e - p * (HH / 4);
+        if (e < kChunks && p < m) {
+          const float* src = Jt + ((size_t)(T - 1 - c0 - p) * B + b) * HH;
+          tmp[r] = reinterpret_cast<const v4f*>(src)[off];
+        } else {
+          const int i0 = (off * 4) / H, j0 = off * 4 - i0 * H;   // identity padding
+          tmp[r] = v4f{i0 == j0 ? 1.f : 0.f, i0 == j0 + 1 ? 1.f : 0.f, i0 == j0 + 2 ? 1.f : 0.f,
+                       i0 == j0 + 3 ? 1.f : 0.f};
+        }
+      }
+#pragma unroll
+      for (int r = 0; r < (kChunks + kThreads - 1) / kThreads; ++r) {
+        const int e = tid + r * kThreads;
+        const int p = e / (HH / 4), off = e - p * (HH / 4);
+        if (e < kChunks) reinterpret_cast<v4f*>(mat + p * TS)[off] = tmp[r];
       }
     }
-#pragma unroll
-    for (int r = 0; r < (kChunks + kThreads - 1) / kThreads; ++r) {
-      const int e = tid + r * kThreads;
-      if (e < kChunks) reinterpret_cast<v4f*>(mat)[e] = tmp[r];
-    }
-  }
-  __syncthreads();
-
-  // ---- up-sweep level 0: a[2s+1] <- a[2s+1] a[2s] ---------------------------------------
-  {
-    v4f acc[9];
-    float* A = mat + (2 * slot + 1) * HH;
-    const float* Bm = mat + (2 * slot) * HH;
-    switch (wave) {
-      case 0: level0_compute<0, 3, 0, 3>(A, Bm, q, acc); break;
-      case 1: level0_compute<0, 3, 3, 2>(A, Bm, q, acc); break;
-      case 2: level0_compute<3, 2, 0, 3>(A, Bm, q, acc); break;
-      default: level0_compute<3, 2, 3, 2>(A, Bm, q, acc); break;
-    }
     __syncthreads();
-    switch (wave) {
-      case 0: level0_store<0, 3, 0, 3>(A, q, acc); break;
-      case 1: level0_store<0, 3, 3, 2>(A, q, acc); break;
-      case 2: level0_store<3, 2, 0, 3>(A, q, acc); break;
-      default: level0_store<3, 2, 3, 2>(A, q, acc); break;
-    }
-  }
-  __syncthreads();
-  // ---- up-sweep levels 1..4: pairs (l, r) = (i + 2^d - 1, i + 2^(d+1) - 1) --------------
-#pragma unroll
-  for (int d = 1; d < 5; ++d) {
-    const int npairs = S >> (d + 1);
-    for (int pr = wave; pr < npairs; pr += 4) {
-      const int i = pr << (d + 1);
-      wave_product(mat + (i + (2 << d) - 1) * HH, mat + (i + (1 << d) - 1) * HH, slot, q);
-    }
-    __syncthreads();
-  }
-  float* total = mat + (S - 1) * HH;
-  const size_t me = (size_t)k * B + b;
+    BPPSA_STAMP(1);
 
-  // ---- publish the segment total (interior segments only) -------------------------------
-  if (k > 0 && k < nseg - 1) {
-    float* dst = agg + me * kAggStride;
-    if (tid < HH / 2) publish2(dst + 2 * tid, total[2 * tid], total[2 * tid + 1]);
-    wait_all_memory_ops();
-    __syncthreads();
-    if (tid == 0) store_status(status + me, kTotalReady);
-  }
-
-  // ---- incoming vector, inclusive vector -------------------------------------------------
-  if (wave == 0) {
-    if (k == 0) {
-      if (lane < H) vin[lane] = seed[(size_t)b * H + lane];
-    } else {
-      look_back(k, b, B, status, agg, incl, vin, hdr);
-    }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-    if (lane < H) {
-      const float y = row_dot(total, lane, vin);
-      vout[lane] = y;
-      if (k < nseg - 1) {
-        __hip_atomic_store(incl + me * kIncStride + lane, y, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      } else {                                    // the chain's last output: g[t_min]
-        float* dst = (n == T) ? g0 + (size_t)b * H : G + (size_t)b * H;
-        dst[lane] = y;
+    // ---- up-sweep level 0: a[2s+1] <- a[2s+1] a[2s] -------------------------------------
+    {
+      v4f acc[9];
+      float* A = mat + (2 * slot + 1) * TS;
+      const float* Bm = mat + (2 * slot) * TS;
+      switch (wave) {
+        case 0: level0_compute<0, 3, 0, 3>(A, Bm, q, acc); break;
+        case 1: level0_compute<0, 3, 3, 2>(A, Bm, q, acc); break;
+        case 2: level0_compute<3, 2, 0, 3>(A, Bm, q, acc); break;
+        default: level0_compute<3, 2, 3, 2>(A, Bm, q, acc); break;
+      }
+      __syncthreads();
+      switch (wave) {
+        case 0: level0_store<0, 3, 0, 3>(A, q, acc); break;
+        case 1: level0_store<0, 3, 3, 2>(A, q, acc); break;
+        case 2: level0_store<3, 2, 0, 3>(A, q, acc); break;
+        default: level0_store<3, 2, 3, 2>(A, q, acc); break;
       }
     }
-    if (k < nseg - 1) {
+    __syncthreads();
+    // ---- up-sweep levels 1..4: pairs (l, r) = (i + 2^d - 1, i + 2^(d+1) - 1) ------------
+#pragma unroll
+    for (int d = 1; d < 5; ++d) {
+      const int npairs = S >> (d + 1);
+      for (int pr = wave; pr < npairs; pr += 4) {
+        const int i = pr << (d + 1);
+        wave_product(mat + (i + (2 << d) - 1) * TS, mat + (i + (1 << d) - 1) * TS, slot, q);
+      }
+      __syncthreads();
+    }
+    BPPSA_STAMP(2);
+    float* total = mat + (S - 1) * TS;
+
+    // ---- publish the segment total (interior segments only) -----------------------------
+    if (k > 0 && k < nseg - 1) {
+      float* dst = agg + me * kAggStride;
+      if (tid < HH / 2) publish2<SCOPE>(dst + 2 * tid, total[2 * tid], total[2 * tid + 1]);
       wait_all_memory_ops();
+      __syncthreads();
+      if (tid == 0) store_status<SCOPE>(status + me, kTotalReady);
+    }
+
+    BPPSA_STAMP(3);
+    // ---- incoming vector, inclusive vector -----------------------------------------------
+    if (wave == 0) {
+      if (k == 0) {
+        if (lane < H) vin[lane] = seed[(size_t)b * H + lane];
+      } else {
+        look_back<SCOPE>(k, b, B, zero, status, agg, incl, vin, hdr);
+      }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
       __builtin_amdgcn_wave_barrier();
-      if (lane == 0) store_status(status + me, kPrefixReady);
-    }
-  }
-  __syncthreads();
-
-  // ---- down-sweep: T <- a[l]; a[l] <- a[r]; a[r] <- T a[r] ------------------------------
-  if (tid < H) vec[(S - 1) * H + tid] = vin[tid];
-  __syncthreads();
-#pragma unroll
-  for (int d = 4; d >= 0; --d) {
-    const int npairs = S >> (d + 1);
-    float res[2];
-    float keep[2];
-#pragma unroll
-    for (int r = 0; r < 2; ++r) {
-      const int e = tid + r * kThreads;
-      res[r] = 0.f;
-      keep[r] = 0.f;
-      if (e < npairs * H) {
-        const int pr = e / H, row = e - pr * H;
-        const int i = pr << (d + 1);
-        const int l = i + (1 << d) - 1, rr = i + (2 << d) - 1;
-        res[r] = row_dot(mat + l * HH, row, vec + rr * H);
-        keep[r] = vec[rr * H + row];
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+      if (lane < H) {
+        const float y = row_dot(total, lane, vin);
+        if (k < nseg - 1) {
+          publish1<SCOPE>(incl + me * kIncStride + lane, y);
+        } else {                                  // the chain's last output: g[t_min]
+          float* dst = (n == T) ? g0 + (size_t)b * H : G + (size_t)b * H;
+          dst[lane] = y;
+        }
+      }
+      if (k < nseg - 1) {
+        wait_all_memory_ops();
+        __builtin_amdgcn_wave_barrier();
+        if (lane == 0) store_status<SCOPE>(status + me, kPrefixReady);
       }
     }
     __syncthreads();
-#pragma unroll
-    for (int r = 0; r < 2; ++r) {
-      const int e = tid + r * kThreads;
-      if (e < npairs * H) {
-        const int pr = e / H, row = e - pr * H;
-        const int i = pr << (d + 1);
-        const int l = i + (1 << d) - 1, rr = i + (2 << d) - 1;
-        vec[l * H + row] = keep[r];
-        vec[rr * H + row] = res[r];
-      }
-    }
-    __syncthreads();
-  }
+    BPPSA_STAMP(4);
 
-  // ---- store: the vector entering element p is g[T-c0-p] = G[T-1-c0-p] --------------------
-  for (int e = tid; e < m * H; e += kThreads) {
-    const int p = e / H, row = e - p * H;
-    __builtin_nontemporal_store(vec[e], G + ((size_t)(T - 1 - c0 - p) * B + b) * H + row);
+    // ---- down-sweep: T <- a[l]; a[l] <- a[r]; a[r] <- T a[r] ----------------------------
+    if (tid < H) vec[(S - 1) * H + tid] = vin[tid];
+    __syncthreads();
+#pragma unroll
+    for (int d = 4; d >= 0; --d) {
+      const int npairs = S >> (d + 1);
+      float res[2];
+      float keep[2];
+#pragma unroll
+      for (int r = 0; r < 2; ++r) {
+        const int e = tid + r * kThreads;
+        res[r] = 0.f;
+        keep[r] = 0.f;
+        if (e < npairs * H) {
+          const int pr = e / H, row = e - pr * H;
+          const int i = pr << (d + 1);
+          const int l = i + (1 << d) - 1, rr = i + (2 << d) - 1;
+          res[r] = row_dot(mat + l * TS, row, vec + rr * H);
+          keep[r] = vec[rr * H + row];
+        }
+      }
+      __syncthreads();
+#pragma unroll
+      for (int r = 0; r < 2; ++r) {
+        const int e = tid + r * kThreads;
+        if (e < npairs * H) {
+          const int pr = e / H, row = e - pr * H;
+          const int i = pr << (d + 1);
+          const int l = i + (1 << d) - 1, rr = i + (2 << d) - 1;
+          vec[l * H + row] = keep[r];
+          vec[rr * H + row] = res[r];
+        }
+      }
+      __syncthreads();
+    }
+
+    BPPSA_STAMP(5);
+    // ---- store: the vector entering element p is g[T-c0-p] = G[T-1-c0-p] ------------------
+    for (int e = tid; e < m * H; e += kThreads) {
+      const int p = e / H, row = e - p * H;
+      __builtin_nontemporal_store(vec[e], G + ((size_t)(T - 1 - c0 - p) * B + b) * H + row);
+    }
+    BPPSA_STAMP(6);
+    __syncthreads();                              // LDS and ticket_s are reused by the next segment
   }
 }
 
 __global__ void clear_kernel(int* p, long long nwords) {
   const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < nwords) p[i] = 0;
+}
+
+int resident_workgroups() {
+  // 3 workgroups of 52.7 KB fit the 160 KB LDS of each of the 256 compute units
+  static int cached = 0;
+  if (!cached) {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+      cus = 256;
+    cached = 3 * cus;
+  }
+  return cached;
 }
 
 }  // namespace
@@ -421,14 +552,26 @@ bppsa_status bppsa_scan_h20(int T, int B, const float* Jt, const float* seed, fl
   if (nblk > 0x7fffffffLL) return BPPSA_EOVERFLOW;
   char* ws = static_cast<char*>(workspace);
   Header* hdr = reinterpret_cast<Header*>(ws);
-  int* status = reinterpret_cast<int*>(ws + 256);
+  int* status = reinterpret_cast<int*>(ws + kHeaderBytes);
   const size_t status_bytes = bppsa_align_up((size_t)nblk * sizeof(int), 256);
-  float* agg = reinterpret_cast<float*>(ws + 256 + status_bytes);
+  float* agg = reinterpret_cast<float*>(ws + kHeaderBytes + status_bytes);
   float* incl = agg + (size_t)nblk * kAggStride;
-  const long long nwords = (256 + (long long)status_bytes) / 4;
+  const long long nwords = (kHeaderBytes + (long long)status_bytes) / 4;
   clear_kernel<<<(int)((nwords + 255) / 256), 256, 0, stream>>>(reinterpret_cast<int*>(ws), nwords);
   BPPSA_CHECK_LAUNCH();
-  scan_h20_kernel<<<(int)nblk, kThreads, 0, stream>>>(T, B, n, nseg, Jt, seed, G, g0, hdr, status, agg, incl);
+  const int resident = resident_workgroups();
+  const int grid = (int)(nblk < resident ? nblk : resident);
+  if (B % kMaxQueues == 0) {
+    scan_h20_kernel<true><<<grid, kThreads, 0, stream>>>(T, B, n, nseg, kMaxQueues, 0, Jt, seed, G, g0, hdr,
+                                                         status, agg, incl BPPSA_TRACE_ARG);
+    BPPSA_CHECK_LAUNCH();
+    // sweep: one workgroup per queue takes whatever is left (nothing, unless a die got no work)
+    scan_h20_kernel<false><<<kMaxQueues, kThreads, 0, stream>>>(T, B, n, nseg, kMaxQueues, 0, Jt, seed, G, g0, hdr,
+                                                                status, agg, incl BPPSA_TRACE_ARG);
+  } else {
+    scan_h20_kernel<false><<<grid, kThreads, 0, stream>>>(T, B, n, nseg, 1, 0, Jt, seed, G, g0, hdr, status,
+                                                          agg, incl BPPSA_TRACE_ARG);
+  }
   BPPSA_CHECK_LAUNCH();
   return BPPSA_OK;
 }

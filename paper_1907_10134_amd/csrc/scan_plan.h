@@ -31,12 +31,13 @@ static inline size_t bppsa_generic_scan_ws(int T, int B, int H, int want_g0) {
 #define BPPSA_H20_SEGMENT 32
 #define BPPSA_H20_AGG_STRIDE 416   /* floats: a 20x20 total padded to 13 cache lines */
 #define BPPSA_H20_INC_STRIDE 32    /* floats: a 20-vector padded to one cache line */
+#define BPPSA_H20_HEADER_BYTES 2048
 
 // Workspace of the single-pass scan: header, one status word, one published total and one
 // published inclusive vector per (segment, sample).
 static inline size_t bppsa_h20_scan_ws(int T, int B) {
   const size_t nblk = (size_t)bppsa_ceil_div(T, BPPSA_H20_SEGMENT) * B;
-  return 256 + bppsa_align_up(nblk * sizeof(int), 256) +
+  return BPPSA_H20_HEADER_BYTES + bppsa_align_up(nblk * sizeof(int), 256) +
          nblk * (BPPSA_H20_AGG_STRIDE + BPPSA_H20_INC_STRIDE) * sizeof(float);
 }
 
