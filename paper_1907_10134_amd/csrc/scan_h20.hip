@@ -146,19 +146,23 @@ __device__ __forceinline__ void wave_product(float* A, const float* Bm, int slot
 }
 
 // y[row] = sum_k M[row][k] x[k], M a 20x20 tile in LDS, x 20 floats in LDS.
+// Four partial sums over k mod 4, combined as (s0 + s1) + (s2 + s3): exactly the arithmetic
+// of a look-back hop, so a segment's inclusive vector has the same bits whether its owner
+// forms it from LDS or a successor forms it from the published total.  That makes the
+// scan's output independent of how far each look-back happened to reach.
 __device__ __forceinline__ float row_dot(const float* M, int row, const float* x) {
   const v4f* m4 = reinterpret_cast<const v4f*>(M + row * H);
   const v4f* x4 = reinterpret_cast<const v4f*>(x);
-  float acc = 0.f;
+  float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
 #pragma unroll
   for (int k4 = 0; k4 < 5; ++k4) {
     const v4f m = m4[k4], xv = x4[k4];
-    acc += m[0] * xv[0];
-    acc += m[1] * xv[1];
-    acc += m[2] * xv[2];
-    acc += m[3] * xv[3];
+    a0 += m[0] * xv[0];
+    a1 += m[1] * xv[1];
+    a2 += m[2] * xv[2];
+    a3 += m[3] * xv[3];
   }
-  return acc;
+  return (a0 + a1) + (a2 + a3);
 }
 
 // Value of `x` in lane `l` (l wave-uniform), as a wave-uniform scalar.
@@ -559,8 +563,14 @@ bppsa_status bppsa_scan_h20(int T, int B, const float* Jt, const float* seed, fl
   const long long nwords = (kHeaderBytes + (long long)status_bytes) / 4;
   clear_kernel<<<(int)((nwords + 255) / 256), 256, 0, stream>>>(reinterpret_cast<int*>(ws), nwords);
   BPPSA_CHECK_LAUNCH();
+  // Persistent grid.  Up to 3 workgroups fit a compute unit, but every workgroup in flight on
+  // a sample lengthens the look-back of that sample's later segments, so the grid is also
+  // capped at 32 workgroups per sample (measured optimum at B = 16: two per compute unit).
   const int resident = resident_workgroups();
-  const int grid = (int)(nblk < resident ? nblk : resident);
+  long long want = 32LL * B;
+  if (want > resident) want = resident;
+  if (want > nblk) want = nblk;
+  const int grid = (int)want;
   if (B % kMaxQueues == 0) {
     scan_h20_kernel<true><<<grid, kThreads, 0, stream>>>(T, B, n, nseg, kMaxQueues, 0, Jt, seed, G, g0, hdr,
                                                          status, agg, incl BPPSA_TRACE_ARG);
