@@ -21,6 +21,25 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E bandwidth
 
 
+# HBM traffic of one scan_h20_kernel launch, from two `rocprofv3 --pmc` runs (FETCH_SIZE, then
+# WRITE_SIZE, KiB per dispatch), each scaled by what the same counter reads for the 768,000,000-byte
+# calibration copy (FETCH_SIZE reads 375,011.6 KiB for 750,000 KiB fetched: scale 2.000; WRITE_SIZE
+# reads 750,010.7 for 750,000 written: scale 1.000).  Offline figures: the counters cannot be read
+# inside this process.  Keyed by (T, B, H); the summaries are the profiles/*.txt of the same workloads.
+PMC_COPY_SCALE = {"FETCH_SIZE": 750000.0 / 375011.5625, "WRITE_SIZE": 750000.0 / 750010.6875}
+PMC_SCAN_KIB = {
+    (1000, 16, 20): {"FETCH_SIZE": 13600.9792, "WRITE_SIZE": 2917.6104},
+    (30000, 16, 20): {"FETCH_SIZE": 402788.0385, "WRITE_SIZE": 113178.5168},
+}
+
+
+def measured_traffic_bytes(T, B, H):
+    kib = PMC_SCAN_KIB.get((T, B, H))
+    if kib is None:
+        return None
+    return int(round(1024 * sum(kib[c] * PMC_COPY_SCALE[c] for c in kib)))
+
+
 def scan_algorithmic_bytes(T, B, H):
     """Each Jacobian read once, each gradient written once, the seed read once."""
     return T * B * (4 * H * H + 4 * H) + 4 * B * H
@@ -111,7 +130,27 @@ def long_scan(bp, workloads, steps):
     gbps = nbytes / (ms * 1e-3) / 1e9
     return {"workload": "rnn_tanh_H20_I1_T30000_B16 (configs[2])", "scan_ms": round(ms, 5),
             "algorithmic_bytes": nbytes, "gbps": round(gbps, 2),
-            "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 5)}
+            "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 5),
+            "traffic": measured_traffic_bytes(w2["T"], w2["B"], w2["H"])}
+
+
+def copy_calibration(bp, steps):
+    """A plain copy of exactly the bytes of configs[2]'s Jacobian array (768,000,000 B each way)."""
+    import torch
+    n = 30000 * 16 * 20 * 20
+    src = torch.ones(n, dtype=torch.float32, device="cuda")
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        bp.calibration_copy(src, dst)
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    for a, z in evs:
+        a.record()
+        bp.calibration_copy(src, dst)
+        z.record()
+    torch.cuda.synchronize()
+    ms = statistics.mean(a.elapsed_time(z) for a, z in evs)
+    return {"workload": "calibration copy", "bytes_read": 4 * n, "bytes_written": 4 * n,
+            "copy_ms": round(ms, 5), "gbps_read_plus_write": round(8 * n / (ms * 1e-3) / 1e9, 2)}
 
 
 def cpu_baseline(w, budget_s=15.0):
@@ -141,6 +180,9 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--long-only", action="store_true",
                     help="time only the T=30000 scan (for profiling); prints its JSON object")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run only the known-size copy kernel (768 MB in, 768 MB out) that "
+                         "hardware traffic counters are scaled against; prints its JSON object")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); "
@@ -157,6 +199,9 @@ def main():
 
     if args.long_only:
         print(json.dumps(long_scan(bp, workloads, args.steps)))
+        return
+    if args.copy_calibration:
+        print(json.dumps(copy_calibration(bp, max(5, min(50, args.steps)))))
         return
 
     w = workloads.config_inputs(1)
@@ -185,7 +230,7 @@ def main():
         "scan_gbps": round(scan_gbps, 2),
         "roofline": {"kernel": "bppsa_scan", "bound": "hbm", "achieved": round(scan_gbps, 2),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(scan_gbps / HBM_PEAK_GBPS, 5),
-                     "traffic": None, "algorithmic_bytes": scan_bytes},
+                     "traffic": measured_traffic_bytes(T, B, H), "algorithmic_bytes": scan_bytes},
     }
 
     if not args.no_long:

@@ -260,6 +260,20 @@ bppsa_status bppsa_spscan_run(const bppsa_spscan_plan* plan, const bppsa_csr* Jt
 bppsa_status bppsa_spscan(int n, const bppsa_csr* Jt, const float* seed, float* const* grads,
                           int up_levels, void* workspace, size_t workspace_bytes, void* stream);
 
+/* ------------------------------------------------------------------------
+ * Measurement aid (not part of the method).
+ * ---------------------------------------------------------------------- */
+
+/*
+ * Plain streaming copy dst[i] = src[i] of n fp32 values (n a multiple of 4,
+ * both pointers 16-byte aligned, non-overlapping).  It moves exactly 4n bytes
+ * in and 4n bytes out of HBM, which makes it the unit against which hardware
+ * traffic counters are scaled when the scan's HBM traffic is reported.
+ * Errors: BPPSA_EINVAL (null pointer, n < 1), BPPSA_ESHAPE (n % 4 != 0 or a
+ * misaligned pointer).
+ */
+bppsa_status bppsa_calibration_copy(const float* src, float* dst, int64_t n, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -84,6 +84,8 @@ def _load():
     lib.bppsa_spscan.restype = c_int
     lib.bppsa_spscan.argtypes = [c_int, ctypes.POINTER(CsrDesc), c_void_p, ctypes.POINTER(c_void_p),
                                  c_int, c_void_p, c_size_t, c_void_p]
+    lib.bppsa_calibration_copy.restype = c_int
+    lib.bppsa_calibration_copy.argtypes = [c_void_p, c_void_p, ctypes.c_int64, c_void_p]
     return lib
 
 
@@ -374,3 +376,12 @@ def spscan(jts, seed, grads, up_levels, workspace, stream=None):
     _check(_lib.bppsa_spscan(len(jts), descs, _ptr(seed), _grads_array(grads), int(up_levels),
                              workspace.data_ptr(), workspace.numel(), _stream(stream)), "bppsa_spscan")
     return grads
+
+
+def calibration_copy(src, dst, stream=None):
+    """dst[:] = src for two fp32 tensors of equal size: the known-size copy used to scale traffic counters."""
+    if src.numel() != dst.numel():
+        raise ValueError("calibration_copy: sizes differ")
+    _check(_lib.bppsa_calibration_copy(_ptr(src, name="src"), _ptr(dst, name="dst"), src.numel(),
+                                       _stream(stream)), "bppsa_calibration_copy")
+    return dst

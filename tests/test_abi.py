@@ -90,3 +90,16 @@ def test_bench_refuses_more_than_one_gpu():
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"],
                        capture_output=True, text=True)
     assert r.returncode != 0 and "one GPU" in r.stderr
+
+
+@pytest.mark.gpu
+def test_calibration_copy_copies_exactly():
+    import torch
+    import paper_1907_10134_amd as bp
+    src = torch.arange(4 * 100003, dtype=torch.float32, device="cuda")
+    dst = torch.zeros_like(src)
+    bp.calibration_copy(src, dst)
+    torch.cuda.synchronize()
+    assert torch.equal(src, dst)
+    with pytest.raises(bp.BppsaError):
+        bp.calibration_copy(src[:6], dst[:6])
