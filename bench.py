@@ -153,6 +153,58 @@ def copy_calibration(bp, steps):
             "copy_ms": round(ms, 5), "gbps_read_plus_write": round(8 * n / (ms * 1e-3) / 1e9, 2)}
 
 
+def gru_workload(bp, workloads, steps):
+    """configs[3] (GRU H=128, T=4096, B=16): per-call times of the three hot-path calls.
+
+    The scan is bound by the fp32 matrix cores here: (nseg - 2) interior segments of S steps
+    each cost S - 1 matrix-matrix products of 2 H^3 FLOP per sample."""
+    import torch
+    w = workloads.config_inputs(3)
+    T, B, H, I = w["T"], w["B"], w["H"], w["I"]
+    d = {k: torch.from_numpy(w[k]).cuda() for k in ("x", "w_ih", "w_hh", "b_ih", "b_hh", "w_out", "b_out", "labels")}
+    h = torch.zeros((T + 1, B, H), dtype=torch.float32, device="cuda")
+    bp.forward(bp.GRU, d["x"], d["w_ih"], d["w_hh"], d["b_ih"], d["b_hh"], h)
+    seed, _ = bp.head_seed(h[-1].contiguous(), d["w_out"], d["b_out"], d["labels"])
+    Jt = torch.empty((T, B, H, H), dtype=torch.float32, device="cuda")
+    G = torch.empty((T, B, H), dtype=torch.float32, device="cuda")
+    ws = torch.empty(bp.scan_workspace_bytes(T, B, H), dtype=torch.uint8, device="cuda")
+    pws = torch.empty(max(bp.param_grads_workspace_bytes(bp.GRU, T, B, H, I), 256), dtype=torch.uint8, device="cuda")
+    out = (torch.empty((3 * H, I), device="cuda"), torch.empty((3 * H, H), device="cuda"),
+           torch.empty((3 * H,), device="cuda"), torch.empty((3 * H,), device="cuda"))
+
+    def step(ev=None):
+        if ev:
+            ev[0].record()
+        bp.build_jacobians(bp.GRU, h, d["x"], d["w_ih"], d["w_hh"], d["b_ih"], d["b_hh"], Jt=Jt)
+        if ev:
+            ev[1].record()
+        bp.scan(Jt, seed, G=G, g0=None, workspace=ws)
+        if ev:
+            ev[2].record()
+        bp.param_grads(bp.GRU, h, d["x"], G, d["w_ih"], d["w_hh"], d["b_ih"], d["b_hh"], out=out, workspace=pws)
+        if ev:
+            ev[3].record()
+
+    steps = max(3, min(10, steps))
+    step()
+    torch.cuda.synchronize()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(steps)]
+    for e in evs:
+        step(e)
+    torch.cuda.synchronize()
+    parts = {name: statistics.mean(e[i].elapsed_time(e[i + 1]) for e in evs)
+             for i, name in enumerate(("build_jacobians_ms", "scan_ms", "param_grads_ms"))}
+    S = 64
+    nseg = -(-(T - 1) // S)
+    mm = (nseg - 2) * (S - 1) * B
+    flop = mm * 2 * H ** 3 + T * B * 2 * H * H
+    tf = flop / (parts["scan_ms"] * 1e-3) / 1e12
+    return {"workload": "gru_H128_I1_T4096_B16 (configs[3])", **{k: round(v, 4) for k, v in parts.items()},
+            "scan_matrix_products": mm, "scan_flop": flop, "scan_tflops": round(tf, 2),
+            "frac_of_fp32_mfma_peak": round(tf / 157.3, 4),
+            "scan_bytes_min": T * B * (4 * H * H + 4 * H), "jacobian_bytes": 4 * T * B * H * H}
+
+
 def cpu_baseline(w, budget_s=15.0):
     """The fp64 oracle's backward (chain + parameter sums) on the same workload, one thread."""
     import numpy as np
@@ -180,6 +232,8 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--long-only", action="store_true",
                     help="time only the T=30000 scan (for profiling); prints its JSON object")
+    ap.add_argument("--gru", action="store_true",
+                    help="time the three calls on configs[3] (GRU H=128, T=4096); prints its JSON object")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only the known-size copy kernel (768 MB in, 768 MB out) that "
                          "hardware traffic counters are scaled against; prints its JSON object")
@@ -199,6 +253,9 @@ def main():
 
     if args.long_only:
         print(json.dumps(long_scan(bp, workloads, args.steps)))
+        return
+    if args.gru:
+        print(json.dumps(gru_workload(bp, workloads, args.steps)))
         return
     if args.copy_calibration:
         print(json.dumps(copy_calibration(bp, max(5, min(50, args.steps)))))

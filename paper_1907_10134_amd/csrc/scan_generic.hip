@@ -133,6 +133,7 @@ int lanes_per_row(int H) {
 bppsa_status launch_reduce(int T, int B, int H, int t_min, int S, int seg_begin, int seg_count,
                            const float* Jt, float* tot, hipStream_t s) {
   if (seg_count <= 0) return BPPSA_OK;
+  if (H == 128) return bppsa_reduce_h128(T, B, t_min, S, seg_begin, seg_count, Jt, tot, s);
   const size_t lds = (size_t)2 * H * H * sizeof(float);
   dim3 grid(seg_count, B);
   const int HH = H * H;
@@ -156,6 +157,8 @@ bppsa_status launch_apply(int T, int B, int H, int t_min, int S, int seg_begin, 
                           const float* Jt, const float* vin, int vin_is_seed,
                           float* G, float* g0, float* v_out, hipStream_t s) {
   if (seg_count <= 0) return BPPSA_OK;
+  if (H == 128)
+    return bppsa_apply_h128(T, B, t_min, S, seg_begin, seg_count, Jt, vin, vin_is_seed, G, g0, v_out, s);
   dim3 grid(seg_count, B);
   apply_segments_kernel<<<grid, kThreads, (size_t)2 * H * sizeof(float), s>>>(
       T, B, H, t_min, S, seg_begin, lanes_per_row(H), Jt, vin, vin_is_seed, G, g0, v_out);

@@ -46,3 +46,10 @@ bppsa_status bppsa_scan_h20(int T, int B, const float* Jt, const float* seed, fl
 
 bppsa_status bppsa_scan_generic(int T, int B, int H, const float* Jt, const float* seed,
                                 float* G, float* g0, void* workspace, hipStream_t stream);
+
+// ---- matrix-core kernels for H = 128 (used by the generic scan's reduce and apply steps) ----
+bppsa_status bppsa_reduce_h128(int T, int B, int t_min, int S, int seg_begin, int seg_count,
+                               const float* Jt, float* tot, hipStream_t s);
+bppsa_status bppsa_apply_h128(int T, int B, int t_min, int S, int seg_begin, int seg_count,
+                              const float* Jt, const float* vin, int vin_is_seed, float* G, float* g0,
+                              float* v_out, hipStream_t s);
