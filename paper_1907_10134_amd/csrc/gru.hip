@@ -264,12 +264,21 @@ size_t deltas_lds_bytes(int H) {
 
 }  // namespace
 
+// matrix-core variants for H = 128
+bppsa_status bppsa_build_jacobians_gru_h128(int T, int B, int I, const float* h, const float* x,
+                                            const float* w_ih, const float* w_hh, const float* b_ih,
+                                            const float* b_hh, float* Jt, hipStream_t stream);
+bppsa_status bppsa_gru_deltas_h128(long long rows, int I, const float* h, const float* x, const float* G,
+                                   const float* w_ih, const float* w_hh, const float* b_ih,
+                                   const float* b_hh, float* delta, hipStream_t stream);
+
 bppsa_status bppsa_build_jacobians_gru(int T, int B, int H, int I,
                                        const float* h, const float* x,
                                        const float* w_ih, const float* w_hh,
                                        const float* b_ih, const float* b_hh,
                                        float* Jt, hipStream_t stream) {
   if (H > 128) return BPPSA_EUNSUPPORTED;
+  if (H == 128) return bppsa_build_jacobians_gru_h128(T, B, I, h, x, w_ih, w_hh, b_ih, b_hh, Jt, stream);
   const long long rows = (long long)T * B;
   const long long nblk = (rows + kRows - 1) / kRows;
   if (nblk > 0x7fffffffLL) return BPPSA_EOVERFLOW;
@@ -307,11 +316,16 @@ bppsa_status bppsa_param_grads_gru(int T, int B, int H, int I,
   const long long nblk = (rows + kRows - 1) / kRows;
   if (nblk > 0x7fffffffLL) return BPPSA_EOVERFLOW;
   size_t lds = deltas_lds_bytes(H);
-  if (lds > 48 * 1024)
-    BPPSA_HIP_TRY(hipFuncSetAttribute((const void*)gru_deltas_kernel,
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-  gru_deltas_kernel<<<(int)nblk, kThreads, lds, stream>>>(rows, H, I, h, x, G, w_ih, w_hh, b_ih, b_hh, delta);
-  BPPSA_CHECK_LAUNCH();
+  if (H == 128) {
+    const bppsa_status st = bppsa_gru_deltas_h128(rows, I, h, x, G, w_ih, w_hh, b_ih, b_hh, delta, stream);
+    if (st != BPPSA_OK) return st;
+  } else {
+    if (lds > 48 * 1024)
+      BPPSA_HIP_TRY(hipFuncSetAttribute((const void*)gru_deltas_kernel,
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    gru_deltas_kernel<<<(int)nblk, kThreads, lds, stream>>>(rows, H, I, h, x, G, w_ih, w_hh, b_ih, b_hh, delta);
+    BPPSA_CHECK_LAUNCH();
+  }
 
   const int ns = gru_splits(rows);
   long long rps = (rows + ns - 1) / ns;
