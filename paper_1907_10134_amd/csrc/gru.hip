@@ -271,6 +271,8 @@ bppsa_status bppsa_build_jacobians_gru_h128(int T, int B, int I, const float* h,
 bppsa_status bppsa_gru_deltas_h128(long long rows, int I, const float* h, const float* x, const float* G,
                                    const float* w_ih, const float* w_hh, const float* b_ih,
                                    const float* b_hh, float* delta, hipStream_t stream);
+bppsa_status bppsa_gru_param_partials_h128(long long rows, int I, int nsplit, const float* h, const float* x,
+                                           const float* delta, float* part, hipStream_t stream);
 
 bppsa_status bppsa_build_jacobians_gru(int T, int B, int H, int I,
                                        const float* h, const float* x,
@@ -332,6 +334,10 @@ bppsa_status bppsa_param_grads_gru(int T, int B, int H, int I,
   rps = (rps + kTileRows - 1) / kTileRows * kTileRows;
   dim3 grid(bppsa_ceil_div(3 * H, kGateTile), ns);
   lds = ((size_t)2 * kTileRows * kGateTile + (size_t)kTileRows * W) * sizeof(float);
+  if (H == 128 && I <= 4) {
+    const bppsa_status st = bppsa_gru_param_partials_h128(rows, I, ns, h, x, delta, part, stream);
+    if (st != BPPSA_OK) return st;
+  } else {
 #define BPPSA_LAUNCH_GRU_PART(M)                                                         \
   gru_param_partials_kernel<M><<<grid, kThreads, lds, stream>>>(rows, H, I, (int)rps, h, x, delta, part)
   if (E <= 2 * kThreads) BPPSA_LAUNCH_GRU_PART(2);
@@ -339,7 +345,8 @@ bppsa_status bppsa_param_grads_gru(int T, int B, int H, int I,
   else if (E <= 17 * kThreads) BPPSA_LAUNCH_GRU_PART(17);
   else BPPSA_LAUNCH_GRU_PART(32);
 #undef BPPSA_LAUNCH_GRU_PART
-  BPPSA_CHECK_LAUNCH();
+    BPPSA_CHECK_LAUNCH();
+  }
   const int Etot = 3 * H * W;
   gru_param_finish_kernel<<<bppsa_ceil_div(Etot, 4), kThreads, 0, stream>>>(ns, H, I, part, dW_ih, dW_hh, db_ih, db_hh);
   BPPSA_CHECK_LAUNCH();

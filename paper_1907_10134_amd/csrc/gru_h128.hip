@@ -177,6 +177,87 @@ gru_deltas_h128_kernel(long long rows, int I, const float* __restrict__ h, const
                  });
 }
 
+// Partial sums of the GRU parameter gradients (Eq. 2, summed over steps and samples):
+//   dW_hh[g][c] = sum_rows Dh[row][g] h'[row][c],  db_hh[g] = sum_rows Dh[row][g],
+//   dW_ih[g][i] = sum_rows Di[row][g] x[row][i],   db_ih[g] = sum_rows Di[row][g],
+// with Dh = (dR, dZ, dM) and Di = (dR, dZ, dN).  The first is a [384 x rows] x [rows x 128]
+// product: every wave owns a strip of 32 gates and a range of rows and accumulates the four
+// 32 x 32 blocks of its strip with 32x32x2 fp32 MFMA, both operands coming straight from
+// global memory (lane l supplies Dh[row][g0 + l % 32] and h'[row][32 cb + l % 32], the lane
+// half choosing which of the two rows of the issue).  The bias and input columns are running
+// sums of the A operand in the same lanes.  Each wave writes its own partial, laid out
+// [3H][H + 1 + I + 1] like the generic kernel's, for the shared finishing kernel.
+constexpr int kPartMaxI = 4;
+
+__global__ void __launch_bounds__(256)
+gru_param_partials_h128_kernel(long long rows, int I, int nsplit, long long rows_per_split,
+                               const float* __restrict__ h, const float* __restrict__ x,
+                               const float* __restrict__ delta, float* __restrict__ part) {
+  const int lane = threadIdx.x & 63, l32 = lane & 31, hs = lane >> 5;
+  const int split = blockIdx.y * 4 + (threadIdx.x >> 6);
+  if (split >= nsplit) return;                 // whole wave
+  const int g0 = blockIdx.x * 32;
+  const int W = H + 1 + I + 1;
+  const int colh = (g0 < 2 * H) ? g0 + l32 : g0 + H + l32;   // dM sits after dN
+  const int coli = g0 + l32;
+  const long long r_begin = (long long)split * rows_per_split;
+  long long r_end = r_begin + rows_per_split;
+  if (r_end > rows) r_end = rows;
+  v16f acc[4];
+#pragma unroll
+  for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[cb][v] = 0.f;
+  float sum_h = 0.f, sum_i = 0.f, sum_x[kPartMaxI];
+#pragma unroll
+  for (int i = 0; i < kPartMaxI; ++i) sum_x[i] = 0.f;
+  for (long long r = r_begin; r < r_end; r += 16) {
+    float a[8], ai[8], b[8][4], xv[8][kPartMaxI];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const long long row = r + 2 * u + hs;
+      const bool ok = row < r_end;
+      const float* d = delta + (size_t)row * 4 * H;
+      a[u] = ok ? d[colh] : 0.f;
+      ai[u] = ok ? d[coli] : 0.f;
+#pragma unroll
+      for (int cb = 0; cb < 4; ++cb) b[u][cb] = ok ? h[(size_t)row * H + 32 * cb + l32] : 0.f;
+#pragma unroll
+      for (int i = 0; i < kPartMaxI; ++i) xv[u][i] = (ok && i < I) ? x[(size_t)row * I + i] : 0.f;
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+#pragma unroll
+      for (int cb = 0; cb < 4; ++cb)
+        acc[cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u], b[u][cb], acc[cb], 0, 0, 0);
+      sum_h += a[u];
+      sum_i += ai[u];
+#pragma unroll
+      for (int i = 0; i < kPartMaxI; ++i) sum_x[i] += ai[u] * xv[u][i];
+    }
+  }
+  float* dst = part + ((size_t)split * 3 * H + g0) * W;
+#pragma unroll
+  for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int g = 8 * (v >> 2) + 4 * hs + (v & 3);
+      dst[(size_t)g * W + 32 * cb + l32] = acc[cb][v];
+    }
+  sum_h += __shfl_xor(sum_h, 32);
+  sum_i += __shfl_xor(sum_i, 32);
+#pragma unroll
+  for (int i = 0; i < kPartMaxI; ++i) sum_x[i] += __shfl_xor(sum_x[i], 32);
+  if (hs == 0) {
+    float* drow = dst + (size_t)l32 * W;
+    drow[H] = sum_h;
+#pragma unroll
+    for (int i = 0; i < kPartMaxI; ++i)
+      if (i < I) drow[H + 1 + i] = sum_x[i];
+    drow[H + 1 + I] = sum_i;
+  }
+}
+
 }  // namespace
 
 bppsa_status bppsa_build_jacobians_gru_h128(int T, int B, int I, const float* h, const float* x,
@@ -205,6 +286,18 @@ bppsa_status bppsa_gru_deltas_h128(long long rows, int I, const float* h, const 
   if (nbatch > 0x7fffffffLL) return BPPSA_EOVERFLOW;
   gru_deltas_h128_kernel<<<(int)nbatch, kDeltaThreads, 0, stream>>>(rows, I, h, x, G, w_ih, w_hh, b_ih, b_hh,
                                                                    delta);
+  BPPSA_CHECK_LAUNCH();
+  return BPPSA_OK;
+}
+
+// `part` receives nsplit partials of [3H][H + 1 + I + 1]; returns BPPSA_EUNSUPPORTED for I > 4.
+bppsa_status bppsa_gru_param_partials_h128(long long rows, int I, int nsplit, const float* h, const float* x,
+                                           const float* delta, float* part, hipStream_t stream) {
+  if (I > kPartMaxI) return BPPSA_EUNSUPPORTED;
+  long long rps = (rows + nsplit - 1) / nsplit;
+  rps = (rps + 1) / 2 * 2;
+  gru_param_partials_h128_kernel<<<dim3(3 * H / 32, (nsplit + 3) / 4), 256, 0, stream>>>(rows, I, nsplit, rps, h, x,
+                                                                                         delta, part);
   BPPSA_CHECK_LAUNCH();
   return BPPSA_OK;
 }

@@ -30,7 +30,8 @@ def _gpu_forward(bp, w, d):
     return h
 
 
-SHAPES = [(6, 2, 3, 2), (9, 3, 20, 1), (5, 2, 33, 3), (20, 16, 64, 1), (7, 5, 128, 1), (1, 1, 1, 1), (3, 17, 8, 2)]
+SHAPES = [(6, 2, 3, 2), (9, 3, 20, 1), (5, 2, 33, 3), (20, 16, 64, 1), (7, 5, 128, 1), (1, 1, 1, 1), (3, 17, 8, 2),
+          (9, 3, 128, 3), (11, 2, 128, 5), (300, 3, 128, 2)]
 
 
 @pytest.mark.parametrize("T,B,H,I", SHAPES)
