@@ -205,6 +205,79 @@ def gru_workload(bp, workloads, steps):
             "scan_bytes_min": T * B * (4 * H * H + 4 * H), "jacobian_bytes": 4 * T * B * H * H}
 
 
+def cnn_workload(bp, workloads, steps):
+    """configs[4] (pruned VGG-11-style CNN, one 32x32x3 image): CSR builders, plan, sparse scan.
+
+    Timing only: the layer inputs that decide the ReLU masks and pooling winners are seeded N(0,1)
+    arrays of the right shapes (the parity tests use the real forward activations); the
+    structure of the convolution and fully connected Jacobians does not depend on them."""
+    import numpy as np
+    import torch
+    layers, _, _ = workloads.cnn_layers()
+    rng = np.random.default_rng(1234 + 4)
+    dev = "cuda"
+    prepared = []
+    for L in reversed(layers):                       # scan order: last layer first
+        if L.kind == "conv":
+            prepared.append((L, torch.from_numpy(L.weight).to(dev), torch.from_numpy(L.mask.astype(np.uint8)).to(dev)))
+        elif L.kind == "fc":
+            prepared.append((L, torch.from_numpy(L.weight).to(dev), torch.from_numpy(L.mask.astype(np.uint8)).to(dev)))
+        else:
+            a = rng.standard_normal(L.in_shape).astype(np.float32)
+            prepared.append((L, torch.from_numpy(a).to(dev), None))
+
+    def build():
+        out = []
+        for L, a, m in prepared:
+            if L.kind == "conv":
+                out.append(bp.csr_conv3x3(a, m, L.in_shape[1], L.in_shape[2]))
+            elif L.kind == "fc":
+                out.append(bp.csr_linear(a, m))
+            elif L.kind == "relu":
+                out.append(bp.csr_relu(a.reshape(-1)))
+            else:
+                out.append(bp.csr_maxpool2x2(a))
+        return out
+
+    build()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    jts = build()
+    torch.cuda.synchronize()
+    build_ms = (time.perf_counter() - t0) * 1e3      # includes the host reads of nnz (two-call pattern)
+    nnz = sum(m.nnz for m in jts)
+    rows = sum(m.rows for m in jts)
+    seed = torch.from_numpy(rng.standard_normal(jts[0].cols).astype(np.float32)).to(dev)
+    grads = [torch.empty((m.rows,), dtype=torch.float32, device=dev) for m in jts]
+    arena = torch.empty((1 << 30,), dtype=torch.uint8, device=dev)
+    res = {"workload": "pruned_vgg11_cnn_32x32x3 (configs[4])", "jacobians": len(jts), "nnz": nnz,
+           "csr_bytes": 8 * nnz + 4 * (rows + len(jts)), "build_all_jacobians_ms": round(build_ms, 3)}
+    reps = max(5, min(50, steps))
+    for U in (0, 2):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        plan = bp.SpscanPlan(jts, U, arena)
+        torch.cuda.synchronize()
+        plan_ms = (time.perf_counter() - t0) * 1e3
+        for _ in range(3):
+            plan.run(jts, seed, grads)
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+        for a, z in evs:
+            a.record()
+            plan.run(jts, seed, grads)
+            z.record()
+        torch.cuda.synchronize()
+        run_ms = statistics.mean(a.elapsed_time(z) for a, z in evs)
+        mm, mv = plan.flops()
+        res["up_levels_%d" % U] = {"plan_ms": round(plan_ms, 3), "run_ms": round(run_ms, 4),
+                                   "products": plan.num_products(), "mm_flop": mm, "mv_flop": mv,
+                                   "arena_bytes": plan.arena_used()}
+        plan.close()
+    b = res["csr_bytes"] + 4 * (rows + jts[0].cols)
+    res["spmv_chain_gbps"] = round(b / (res["up_levels_0"]["run_ms"] * 1e-3) / 1e9, 2)
+    return res
+
+
 def cpu_baseline(w, budget_s=15.0):
     """The fp64 oracle's backward (chain + parameter sums) on the same workload, one thread."""
     import numpy as np
@@ -234,6 +307,8 @@ def main():
                     help="time only the T=30000 scan (for profiling); prints its JSON object")
     ap.add_argument("--gru", action="store_true",
                     help="time the three calls on configs[3] (GRU H=128, T=4096); prints its JSON object")
+    ap.add_argument("--cnn", action="store_true",
+                    help="time the sparse path on configs[4] (pruned CNN); prints its JSON object")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only the known-size copy kernel (768 MB in, 768 MB out) that "
                          "hardware traffic counters are scaled against; prints its JSON object")
@@ -256,6 +331,9 @@ def main():
         return
     if args.gru:
         print(json.dumps(gru_workload(bp, workloads, args.steps)))
+        return
+    if args.cnn:
+        print(json.dumps(cnn_workload(bp, workloads, args.steps)))
         return
     if args.copy_calibration:
         print(json.dumps(copy_calibration(bp, max(5, min(50, args.steps)))))
