@@ -111,7 +111,18 @@ size_t bppsa_scan_workspace_bytes(int T, int B, int H);
  * g0 == NULL Jt[0] is never read (Algorithm 1's last input reaches no output).
  * Jt [T,B,H,H], seed [B,H], G [T,B,H], g0 [B,H] or NULL.  T = 1 is legal.
  * Values follow any bracketing of the products (Section 3.5): results agree
- * with sequential back-propagation up to fp32 rounding order.
+ * with sequential back-propagation up to fp32 rounding order; repeated calls
+ * on the same inputs return the same bits.
+ * Kernels: H = 20 runs as one pass over Jt (segments of 32 steps resident in
+ * LDS, Algorithm 1 inside a segment, look-back across segments); H = 128 and
+ * every other H <= 128 run the hybrid of Section 5.3 (segment totals, scan of
+ * the totals, matrix-vector down-sweep); H > 128 yields BPPSA_EUNSUPPORTED.
+ * The workspace is scratch only; its contents before the call do not matter.
+ * For H = 20 its first 4-byte word is an error flag: it is 0 after a normal
+ * call and 1 if a bounded wait inside the kernel expired, in which case G is
+ * invalid (this cannot happen while the device makes progress; the caller may
+ * read the word after synchronising).  Calls that share a workspace must be
+ * ordered on one stream.
  */
 bppsa_status bppsa_scan(int T, int B, int H,
                         const float* Jt, const float* seed,
