@@ -216,19 +216,20 @@ __device__ __forceinline__ void fetch2(const float* src, float& a, float& b) {
 __device__ __forceinline__ void wait_all_memory_ops() { __builtin_amdgcn_s_waitcnt(0); }
 
 // Look-back, run by wave 0.  Leaves the vector entering this segment in vin[0..20).
-// Window: the 64 predecessors k-1 .. k-64 of the same sample.  The nearest one that has
+// Window: the 64 predecessors k-1 .. k-64 of the same sample; status words are stored
+// sample-major so that the window is 256 contiguous bytes (two cache lines per poll).  The nearest one that has
 // published its inclusive vector is the base; every nearer one must have published its
 // total.  Lower tickets are already running or finished, so the wait ends; a bounded spin
 // turns anything unexpected into an error flag instead of a hang.
 template <int SCOPE>
-__device__ void look_back(int k, int b, int B, int zero, int* status, const float* agg, const float* incl,
+__device__ void look_back(int k, int b, int B, int nseg, int zero, int* status, const float* agg, const float* incl,
                           float* vin, Header* hdr) {
   const int lane = threadIdx.x & 63;
   const int idx = k - 1 - lane;
   int f = -1;
   for (unsigned spin = 0;; ++spin) {
     int st = kTotalReady;                       // lanes past segment 0 never block the window
-    if (idx >= 0) st = load_status<SCOPE>(status + (size_t)idx * B + b, zero);
+    if (idx >= 0) st = load_status<SCOPE>(status + (size_t)b * nseg + idx, zero);
     const unsigned long long pmask = __ballot(idx >= 0 && st == kPrefixReady);
     const unsigned long long amask = __ballot(st >= kTotalReady);
     if (pmask) {
@@ -446,7 +447,7 @@ scan_h20_kernel(int T, int B, int n, int nseg, int nq, int zero, const float* __
       if (tid < HH / 2) publish2<SCOPE>(dst + 2 * tid, total[2 * tid], total[2 * tid + 1]);
       wait_all_memory_ops();
       __syncthreads();
-      if (tid == 0) store_status<SCOPE>(status + me, kTotalReady);
+      if (tid == 0) store_status<SCOPE>(status + (size_t)b * nseg + k, kTotalReady);
     }
 
     BPPSA_STAMP(3);
@@ -455,7 +456,7 @@ scan_h20_kernel(int T, int B, int n, int nseg, int nq, int zero, const float* __
       if (k == 0) {
         if (lane < H) vin[lane] = seed[(size_t)b * H + lane];
       } else {
-        look_back<SCOPE>(k, b, B, zero, status, agg, incl, vin, hdr);
+        look_back<SCOPE>(k, b, B, nseg, zero, status, agg, incl, vin, hdr);
       }
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
       __builtin_amdgcn_wave_barrier();
@@ -472,7 +473,7 @@ scan_h20_kernel(int T, int B, int n, int nseg, int nq, int zero, const float* __
       if (k < nseg - 1) {
         wait_all_memory_ops();
         __builtin_amdgcn_wave_barrier();
-        if (lane == 0) store_status<SCOPE>(status + me, kPrefixReady);
+        if (lane == 0) store_status<SCOPE>(status + (size_t)b * nseg + k, kPrefixReady);
       }
     }
     __syncthreads();
@@ -563,12 +564,9 @@ bppsa_status bppsa_scan_h20(int T, int B, const float* Jt, const float* seed, fl
   const long long nwords = (kHeaderBytes + (long long)status_bytes) / 4;
   clear_kernel<<<(int)((nwords + 255) / 256), 256, 0, stream>>>(reinterpret_cast<int*>(ws), nwords);
   BPPSA_CHECK_LAUNCH();
-  // Persistent grid.  Up to 3 workgroups fit a compute unit, but every workgroup in flight on
-  // a sample lengthens the look-back of that sample's later segments, so the grid is also
-  // capped at 32 workgroups per sample (measured optimum at B = 16: two per compute unit).
+  // Persistent grid: as many workgroups as the device holds at once (3 per compute unit).
   const int resident = resident_workgroups();
-  long long want = 32LL * B;
-  if (want > resident) want = resident;
+  long long want = resident;
   if (want > nblk) want = nblk;
   const int grid = (int)want;
   if (B % kMaxQueues == 0) {
