@@ -49,6 +49,34 @@ rnn_jacobians_kernel(long long n_vec, int B, int H,
   }
 }
 
+// H = 20 (the paper's RNN size): a tile is 100 pieces of 16 bytes.  A thread keeps one fixed
+// piece position (row i, columns j4..j4+3), so its four weights live in registers, and walks
+// over tiles: per tile it reads 16 bytes of h, multiplies and issues one 16-byte store.
+// 500 of the 512 threads of a workgroup cover five tiles per pass.
+constexpr int kH20Threads = 512;
+constexpr int kH20TilesPerPass = 5;
+
+typedef float bj_v4f __attribute__((ext_vector_type(4)));
+
+__global__ void __launch_bounds__(kH20Threads)
+rnn_jacobians_h20_kernel(int tiles, int B, const float* __restrict__ h, const float* __restrict__ w_hh,
+                         float* __restrict__ Jt) {
+  constexpr int H = 20;
+  const int tid = threadIdx.x;
+  const int slot = tid / 100, p = tid - slot * 100;
+  if (slot >= kH20TilesPerPass) return;
+  const int i = p / 5, j4 = (p - i * 5) * 4;
+  bj_v4f w;
+#pragma unroll
+  for (int u = 0; u < 4; ++u) w[u] = w_hh[(j4 + u) * H + i];
+  const int step = gridDim.x * kH20TilesPerPass;
+  for (int m = blockIdx.x * kH20TilesPerPass + slot; m < tiles; m += step) {
+    const bj_v4f hv = *reinterpret_cast<const bj_v4f*>(h + (size_t)(m + B) * H + j4);   // h[t+1][b][j4..]
+    const bj_v4f o = w * (1.0f - hv * hv);
+    __builtin_nontemporal_store(o, reinterpret_cast<bj_v4f*>(Jt + (size_t)m * H * H + p * 4));
+  }
+}
+
 }  // namespace
 
 bppsa_status bppsa_build_jacobians_gru(int T, int B, int H, int I,
@@ -72,6 +100,14 @@ extern "C" bppsa_status bppsa_build_jacobians(int cell, int T, int B, int H, int
   }
   if (cell != BPPSA_RNN_TANH) return BPPSA_EUNSUPPORTED;
 
+  if (H == 20 && (long long)T * B < 0x7fffffffLL - 65536) {
+    const int tiles = T * B;
+    int grid = bppsa_ceil_div(tiles, kH20TilesPerPass);
+    if (grid > 2048) grid = 2048;
+    rnn_jacobians_h20_kernel<<<grid, kH20Threads, 0, s>>>(tiles, B, h, w_hh, Jt);
+    BPPSA_CHECK_LAUNCH();
+    return BPPSA_OK;
+  }
   const long long n_elem = (long long)T * B * H * H;
   const int w_in_lds = (size_t)H * H * sizeof(float) <= 64 * 1024;
   const size_t lds = w_in_lds ? (size_t)H * H * sizeof(float) : 0;

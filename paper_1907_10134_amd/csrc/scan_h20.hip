@@ -20,6 +20,8 @@
 //                stored.
 // The chain runs from the seed end: element c is Jt[T-1-c]; the vector that
 // enters element c is g[T-c] = G[T-1-c].
+#include <stdlib.h>
+
 #include "bppsa_internal.h"
 #include "scan_plan.h"
 
@@ -53,6 +55,9 @@ struct Header {          // first kHeaderBytes of the workspace, zeroed before e
   int error;             // set when a bounded wait expired: results are invalid
   int pad[31];
   int ticket[kMaxQueues][32];   // next segment of each queue, one cache line apart
+  // workgroups that have started, per die (slot kMaxQueues: bystanders of the test hook),
+  // one cache line apart
+  int started[kMaxQueues + 1][32];
 };
 static_assert(sizeof(Header) <= kHeaderBytes, "header does not fit");
 
@@ -180,13 +185,12 @@ __device__ __forceinline__ float readlane_f(float x, int l) {
 //               write-through and these accesses miss it, so they are coherent between all
 //               workgroups of ONE die; the kernel uses this only for chains whose segments
 //               all run on the same die (see the queue selection below).
-// A die-local status read is an atomic add of a run-time zero: read-modify-write atomics are
-// always performed in the L2, whereas a workgroup-scope load may be served by the L1 of the
-// compute unit and would then never see another unit's update.
+// Status words are always polled with device-scope loads: those bypass the L1 of the compute
+// unit (a workgroup-scope load may be served by that L1 and would then never see another
+// unit's update) and, for a chain that lives on one die, still hit that die's L2.
 template <int SCOPE>
-__device__ __forceinline__ int load_status(int* p, int zero) {
-  if (SCOPE == __HIP_MEMORY_SCOPE_WORKGROUP) return __hip_atomic_fetch_add(p, zero, __ATOMIC_RELAXED, SCOPE);
-  return __hip_atomic_load(p, __ATOMIC_RELAXED, SCOPE);
+__device__ __forceinline__ int load_status(int* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 template <int SCOPE>
 __device__ __forceinline__ void store_status(int* p, int v) {
@@ -222,14 +226,14 @@ __device__ __forceinline__ void wait_all_memory_ops() { __builtin_amdgcn_s_waitc
 // total.  Lower tickets are already running or finished, so the wait ends; a bounded spin
 // turns anything unexpected into an error flag instead of a hang.
 template <int SCOPE>
-__device__ void look_back(int k, int b, int B, int nseg, int zero, int* status, const float* agg, const float* incl,
+__device__ void look_back(int k, int b, int B, int nseg, int* status, const float* agg, const float* incl,
                           float* vin, Header* hdr) {
   const int lane = threadIdx.x & 63;
   const int idx = k - 1 - lane;
   int f = -1;
   for (unsigned spin = 0;; ++spin) {
     int st = kTotalReady;                       // lanes past segment 0 never block the window
-    if (idx >= 0) st = load_status<SCOPE>(status + (size_t)b * nseg + idx, zero);
+    if (idx >= 0) st = load_status<SCOPE>(status + (size_t)b * nseg + idx);
     const unsigned long long pmask = __ballot(idx >= 0 && st == kPrefixReady);
     const unsigned long long amask = __ballot(st >= kTotalReady);
     if (pmask) {
@@ -324,10 +328,12 @@ __device__ void look_back(int k, int b, int B, int nseg, int zero, int* status, 
 #define BPPSA_STAMP(i) do { if (trace && threadIdx.x == 0) trace[(size_t)me * 16 + (i)] = wall_clock64(); } while (0)
 #define BPPSA_TRACE_PARAM , long long* trace
 #define BPPSA_TRACE_ARG , nullptr
+#define BPPSA_TRACE_FWD , trace
 #else
 #define BPPSA_STAMP(i) do { } while (0)
 #define BPPSA_TRACE_PARAM
 #define BPPSA_TRACE_ARG
+#define BPPSA_TRACE_FWD
 #endif
 
 // Identity of the compute die (XCD) this wave runs on: bits [3:0] of hardware register
@@ -336,33 +342,33 @@ __device__ __forceinline__ int xcc_id() { return __builtin_amdgcn_s_getreg((3 <<
 
 // Work distribution.  The samples are dealt round-robin to `nq` queues (sample b belongs to
 // queue b % nq); a queue hands out its (segment, sample) pairs in chain order through an
-// atomic ticket.  Workgroups are persistent: each drains one queue and exits when it is
+// atomic ticket.  Workgroups are persistent: each drains one queue and leaves when it is
 // empty, so a workgroup only ever waits for tickets that were taken before its own.
 //   LOCAL  - nq = 8 and the queue is chosen by the die the workgroup runs on: every chain
-//            then lives on one die and its look-back traffic stays in that die's L2.
-//   !LOCAL - the queue is blockIdx % nq and all cross-workgroup traffic is device scope.
-//            This form is correct for any placement; it serves batch sizes that are not a
-//            multiple of 8 and, launched after the LOCAL form, picks up whatever a die
-//            that received no workgroups has left behind (normally nothing).
-template <bool LOCAL>
-__global__ void __launch_bounds__(kThreads, 3)
-scan_h20_kernel(int T, int B, int n, int nseg, int nq, int zero, const float* __restrict__ Jt,
-                const float* __restrict__ seed, float* __restrict__ G, float* __restrict__ g0,
-                Header* hdr, int* status, float* agg, float* incl BPPSA_TRACE_PARAM) {
-  constexpr int SCOPE = LOCAL ? __HIP_MEMORY_SCOPE_WORKGROUP : __HIP_MEMORY_SCOPE_AGENT;
-  // 32 tiles, then room so that the 32 down-sweep vectors can start on top of the last tile
-  // (the segment total, dead once the inclusive vector has been formed)
-  __shared__ __attribute__((aligned(16))) float lds[(S - 1) * TS + S * H];
-  __shared__ __attribute__((aligned(16))) float vin[H];
-  __shared__ int ticket_s;
-  float* mat = lds;
-  float* vec = lds + (S - 1) * TS;
+//            then lives on one die and its look-back traffic stays in that die's L2.  The
+//            last workgroup to leave checks that every queue was served by its die; a queue
+//            that was not (its die received no workgroup) is untouched, and that workgroup
+//            drains it alone with device-scope accesses - slow, but correct for any placement.
+//   !LOCAL - the queue is blockIdx % nq and all cross-workgroup traffic is device scope
+//            (batch sizes that are not a multiple of 8).
+struct Shared {
+  float* mat;
+  float* vec;
+  float* vin;
+  int* ticket_s;
+};
 
-  const int qid = LOCAL ? (xcc_id() & (kMaxQueues - 1)) : (int)(blockIdx.x % (unsigned)nq);
-  if (qid >= nq) return;
+template <int SCOPE>
+__device__ __forceinline__ void drain_queue(int qid, int T, int B, int n, int nseg, int nq,
+                                            const float* __restrict__ Jt, const float* __restrict__ seed,
+                                            float* __restrict__ G, float* __restrict__ g0, Header* hdr,
+                                            int* status, float* agg, float* incl, const Shared sh
+                                            BPPSA_TRACE_PARAM) {
+  float* const mat = sh.mat;
+  float* const vec = sh.vec;
+  float* const vin = sh.vin;
   const int bq = (B - qid + nq - 1) / nq;        // samples of this queue: qid, qid + nq, ...
   const int quota = nseg * bq;
-
   for (;;) {
     // Re-derive the lane coordinates inside the loop from an opaque copy of the thread id:
     // otherwise every LDS address of the body is hoisted out of the loop and the hoisted
@@ -370,9 +376,9 @@ scan_h20_kernel(int T, int B, int n, int nseg, int nq, int zero, const float* __
     int tid = threadIdx.x;
     asm volatile("" : "+v"(tid));
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, slot = lane >> 2, q = lane & 3;
-    if (tid == 0) ticket_s = __hip_atomic_fetch_add(&hdr->ticket[qid][0], 1, __ATOMIC_RELAXED, SCOPE);
+    if (tid == 0) *sh.ticket_s = __hip_atomic_fetch_add(&hdr->ticket[qid][0], 1, __ATOMIC_RELAXED, SCOPE);
     __syncthreads();
-    const int ticket = ticket_s;
+    const int ticket = *sh.ticket_s;
     if (ticket >= quota) break;                  // uniform: the queue is empty
     const int k = ticket / bq;                   // segment, 0 = seed end
     const int b = qid + nq * (ticket - k * bq);
@@ -456,7 +462,7 @@ scan_h20_kernel(int T, int B, int n, int nseg, int nq, int zero, const float* __
       if (k == 0) {
         if (lane < H) vin[lane] = seed[(size_t)b * H + lane];
       } else {
-        look_back<SCOPE>(k, b, B, nseg, zero, status, agg, incl, vin, hdr);
+        look_back<SCOPE>(k, b, B, nseg, status, agg, incl, vin, hdr);
       }
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
       __builtin_amdgcn_wave_barrier();
@@ -526,6 +532,60 @@ scan_h20_kernel(int T, int B, int n, int nseg, int nq, int zero, const float* __
   }
 }
 
+template <bool LOCAL>
+__global__ void __launch_bounds__(kThreads, 3)
+scan_h20_kernel(int T, int B, int n, int nseg, int nq, int skip_dies, const float* __restrict__ Jt,
+                const float* __restrict__ seed, float* __restrict__ G, float* __restrict__ g0,
+                Header* hdr, int* status, float* agg, float* incl BPPSA_TRACE_PARAM) {
+  // 32 tiles, then room so that the 32 down-sweep vectors can start on top of the last tile
+  // (the segment total, dead once the inclusive vector has been formed)
+  __shared__ __attribute__((aligned(16))) float lds[(S - 1) * TS + S * H];
+  __shared__ __attribute__((aligned(16))) float vin[H];
+  __shared__ int ticket_s;
+  const Shared sh = {lds, lds + (S - 1) * TS, vin, &ticket_s};
+  if (!LOCAL) {
+    const int qid = (int)(blockIdx.x % (unsigned)nq);
+    drain_queue<__HIP_MEMORY_SCOPE_AGENT>(qid, T, B, n, nseg, nq, Jt, seed, G, g0, hdr, status, agg, incl, sh
+                                          BPPSA_TRACE_FWD);
+    return;
+  }
+  const int qid = xcc_id() & (kMaxQueues - 1);
+  // skip_dies is 0 in normal use; a test sets bits to make the workgroups of those dies stand
+  // aside, which exercises the fallback below
+  const bool aside = ((skip_dies >> qid) & 1) != 0;
+  // Count this workgroup in for its die.  The result is not used, so the wave does not wait
+  // for the (device-scope, hence slow) atomic; it only has to land before this workgroup ends.
+  if (threadIdx.x == 0)
+    __hip_atomic_fetch_add(&hdr->started[aside ? kMaxQueues : qid][0], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  if (!aside)
+    drain_queue<__HIP_MEMORY_SCOPE_WORKGROUP>(qid, T, B, n, nseg, nq, Jt, seed, G, g0, hdr, status, agg, incl, sh
+                                              BPPSA_TRACE_FWD);
+  // A queue whose die received no workgroup is untouched.  That is certain only once every
+  // workgroup of the grid has started; the workgroups that find this to be the case when they
+  // run out of work (the last one to finish always does, because every workgroup waits for its
+  // own count to land before it ends) drain such queues together with device-scope accesses.
+  __syncthreads();                               // every thread has read the final ticket
+  if (threadIdx.x == 0) {
+    wait_all_memory_ops();
+    int total = 0, unserved = 0;
+#pragma unroll
+    for (int q = 0; q <= kMaxQueues; ++q) {
+      const int c = __hip_atomic_load(&hdr->started[q][0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      total += c;
+      if (q < kMaxQueues && c == 0) unserved |= 1 << q;
+    }
+    ticket_s = (total == (int)gridDim.x) ? unserved : 0;
+  }
+  __syncthreads();
+  const int unserved = ticket_s;
+  __syncthreads();
+  for (int q = 0; q < kMaxQueues; ++q) {
+    if ((unserved >> q) & 1)
+      drain_queue<__HIP_MEMORY_SCOPE_AGENT>(q, T, B, n, nseg, nq, Jt, seed, G, g0, hdr, status, agg, incl, sh
+                                            BPPSA_TRACE_FWD);
+  }
+}
+
 __global__ void clear_kernel(int* p, long long nwords) {
   const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < nwords) p[i] = 0;
@@ -565,17 +625,17 @@ bppsa_status bppsa_scan_h20(int T, int B, const float* Jt, const float* seed, fl
   clear_kernel<<<(int)((nwords + 255) / 256), 256, 0, stream>>>(reinterpret_cast<int*>(ws), nwords);
   BPPSA_CHECK_LAUNCH();
   // Persistent grid: as many workgroups as the device holds at once (3 per compute unit).
+  // BPPSA_H20_SKIP_DIES (a bit mask, tests only) makes the workgroups of the named dies stand
+  // aside so that the last workgroup's device-scope fallback runs.
+  const char* skip_env = getenv("BPPSA_H20_SKIP_DIES");
+  const int skip_dies = skip_env ? atoi(skip_env) & 0xff : 0;
   const int resident = resident_workgroups();
   long long want = resident;
   if (want > nblk) want = nblk;
   const int grid = (int)want;
   if (B % kMaxQueues == 0) {
-    scan_h20_kernel<true><<<grid, kThreads, 0, stream>>>(T, B, n, nseg, kMaxQueues, 0, Jt, seed, G, g0, hdr,
+    scan_h20_kernel<true><<<grid, kThreads, 0, stream>>>(T, B, n, nseg, kMaxQueues, skip_dies, Jt, seed, G, g0, hdr,
                                                          status, agg, incl BPPSA_TRACE_ARG);
-    BPPSA_CHECK_LAUNCH();
-    // sweep: one workgroup per queue takes whatever is left (nothing, unless a die got no work)
-    scan_h20_kernel<false><<<kMaxQueues, kThreads, 0, stream>>>(T, B, n, nseg, kMaxQueues, 0, Jt, seed, G, g0, hdr,
-                                                                status, agg, incl BPPSA_TRACE_ARG);
   } else {
     scan_h20_kernel<false><<<grid, kThreads, 0, stream>>>(T, B, n, nseg, 1, 0, Jt, seed, G, g0, hdr, status,
                                                           agg, incl BPPSA_TRACE_ARG);

@@ -31,7 +31,7 @@ static inline size_t bppsa_generic_scan_ws(int T, int B, int H, int want_g0) {
 #define BPPSA_H20_SEGMENT 32
 #define BPPSA_H20_AGG_STRIDE 416   /* floats: a 20x20 total padded to 13 cache lines */
 #define BPPSA_H20_INC_STRIDE 32    /* floats: a 20-vector padded to one cache line */
-#define BPPSA_H20_HEADER_BYTES 2048
+#define BPPSA_H20_HEADER_BYTES 4096
 
 // Workspace of the single-pass scan: header, one status word, one published total and one
 // published inclusive vector per (segment, sample).

@@ -165,3 +165,22 @@ def test_end_to_end_norm_preserving(bp, T):
     assert per_step_err(G, G_ref) <= 100 * TOL
     for got, ref in zip(grads[:3], grads_ref):
         assert rel_err(got, ref) <= TOL
+
+
+@pytest.mark.parametrize("mask", [0x01, 0xA5, 0xFF])
+def test_scan_h20_fallback_when_dies_stand_aside(bp, mask, monkeypatch):
+    """Chains whose compute die takes no part are picked up by the last workgroup (device-scope path)."""
+    import torch
+    T, B, H = 200, 16, 20
+    jt, seed = workloads.random_jacobian_chain(T, B, H, seed=77, scale=1.05 / np.sqrt(H))
+    G_ref, _ = oscan.linear_scan(jt, seed)
+    djt, dseed = to_gpu(jt), to_gpu(seed)
+    G_normal = to_np(bp.scan(djt, dseed))
+    monkeypatch.setenv("BPPSA_H20_SKIP_DIES", str(mask))
+    ws = torch.zeros(bp.scan_workspace_bytes(T, B, H), dtype=torch.uint8, device="cuda")
+    G = to_np(bp.scan(djt, dseed, workspace=ws))
+    torch.cuda.synchronize()
+    monkeypatch.delenv("BPPSA_H20_SKIP_DIES")
+    assert int(ws[:4].view(torch.int32).item()) == 0          # no bounded wait expired
+    assert rel_err(G, G_ref) <= TOL
+    assert np.array_equal(G, G_normal)                        # same bits as the die-local path
