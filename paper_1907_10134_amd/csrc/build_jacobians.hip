@@ -103,7 +103,7 @@ extern "C" bppsa_status bppsa_build_jacobians(int cell, int T, int B, int H, int
   if (H == 20 && (long long)T * B < 0x7fffffffLL - 65536) {
     const int tiles = T * B;
     int grid = bppsa_ceil_div(tiles, kH20TilesPerPass);
-    if (grid > 2048) grid = 2048;
+    if (grid > 512) grid = 512;
     rnn_jacobians_h20_kernel<<<grid, kH20Threads, 0, s>>>(tiles, B, h, w_hh, Jt);
     BPPSA_CHECK_LAUNCH();
     return BPPSA_OK;

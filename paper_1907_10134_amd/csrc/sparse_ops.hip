@@ -146,20 +146,115 @@ spgemm_symbolic_kernel(int words, const int32_t* __restrict__ a_indptr,
   }
 }
 
-// C's row is owned by one workgroup: clear it, then scatter the products with atomic adds
-// into the position found by binary search in the (ascending) column indices.
+// C's row is owned by one workgroup and accumulated in 48 KB of LDS (three workgroups per
+// compute unit):
+//   DENSE  - B has at most kNumericCap columns: one accumulator per column, products are
+//            added at acc[col] with LDS atomics and the row's entries are gathered at the end;
+//   !DENSE - rows of up to kNumericCap / 2 entries stage their (ascending) column indices in
+//            LDS, every product finds its slot by binary search there; longer rows take the
+//            same steps directly in global memory.
+constexpr int kNumericCap = 12288;
+
+template <bool DENSE>
 __global__ void __launch_bounds__(256)
-spgemm_numeric_kernel(const int32_t* __restrict__ a_indptr, const int32_t* __restrict__ a_indices,
+spgemm_numeric_kernel(int b_cols, const int32_t* __restrict__ a_indptr, const int32_t* __restrict__ a_indices,
                       const float* __restrict__ a_data, const int32_t* __restrict__ b_indptr,
                       const int32_t* __restrict__ b_indices, const float* __restrict__ b_data,
                       const int32_t* __restrict__ c_indptr, const int32_t* __restrict__ c_indices,
                       float* __restrict__ c_data) {
+  __shared__ float lds[kNumericCap];
   const int row = blockIdx.x;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwave = blockDim.x >> 6;
   const int cs = c_indptr[row], ce = c_indptr[row + 1];
+  const int n = ce - cs;
+  const int as = a_indptr[row], ae = a_indptr[row + 1];
+  if (n == 0) return;
+  if (DENSE) {
+    for (int p = threadIdx.x; p < n; p += blockDim.x) lds[c_indices[cs + p]] = 0.f;
+    __syncthreads();
+    // Each lane first fetches one entry of A's row and the bounds of the matching row of B;
+    // the wave then walks those entries four at a time so that the loads of four rows of B are
+    // in flight together (the rows are short, so one row per trip would leave the wave waiting
+    // on memory most of the time).
+    for (int p0 = as + wave * 64; p0 < ae; p0 += nwave * 64) {
+      const int mine = p0 + lane;
+      int bs_l = 0, be_l = 0;
+      float av_l = 0.f;
+      if (mine < ae) {
+        const int k = a_indices[mine];
+        av_l = a_data[mine];
+        bs_l = b_indptr[k];
+        be_l = b_indptr[k + 1];
+      }
+      const int cnt = (ae - p0 < 64) ? (ae - p0) : 64;
+      for (int e = 0; e < cnt; e += 4) {
+        int bs[4], be[4], col[4];
+        float av[4], bv[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int src = (e + u < cnt) ? e + u : e;
+          bs[u] = __builtin_amdgcn_readlane(bs_l, src);
+          be[u] = (e + u < cnt) ? __builtin_amdgcn_readlane(be_l, src) : bs[u];
+          av[u] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, av_l), src));
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int q = bs[u] + lane;
+          col[u] = (q < be[u]) ? b_indices[q] : -1;
+          bv[u] = (q < be[u]) ? b_data[q] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+          if (col[u] >= 0) atomicAdd(&lds[col[u]], av[u] * bv[u]);
+        for (int u = 0; u < 4; ++u) {             // rows of B longer than one wave: four loads in flight
+          for (int q0 = bs[u] + 64 + lane; q0 < be[u]; q0 += 256) {
+            int c4[4];
+            float v4[4];
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+              const int q = q0 + 64 * w;
+              c4[w] = (q < be[u]) ? b_indices[q] : -1;
+              v4[w] = (q < be[u]) ? b_data[q] : 0.f;
+            }
+#pragma unroll
+            for (int w = 0; w < 4; ++w)
+              if (c4[w] >= 0) atomicAdd(&lds[c4[w]], av[u] * v4[w]);
+          }
+        }
+      }
+    }
+    __syncthreads();
+    for (int p = threadIdx.x; p < n; p += blockDim.x) c_data[cs + p] = lds[c_indices[cs + p]];
+    return;
+  }
+  if (n <= kNumericCap / 2) {
+    float* cacc = lds;
+    int32_t* cidx = reinterpret_cast<int32_t*>(lds + kNumericCap / 2);
+    for (int p = threadIdx.x; p < n; p += blockDim.x) {
+      cidx[p] = c_indices[cs + p];
+      cacc[p] = 0.f;
+    }
+    __syncthreads();
+    for (int p = as + wave; p < ae; p += nwave) {
+      const int k = a_indices[p];
+      const float av = a_data[p];
+      const int bs = b_indptr[k], be = b_indptr[k + 1];
+      for (int q = bs + lane; q < be; q += 64) {
+        const int col = b_indices[q];
+        int lo = 0, hi = n - 1;
+        while (lo < hi) {
+          const int mid = (lo + hi) >> 1;
+          if (cidx[mid] < col) lo = mid + 1; else hi = mid;
+        }
+        atomicAdd(&cacc[lo], av * b_data[q]);
+      }
+    }
+    __syncthreads();
+    for (int p = threadIdx.x; p < n; p += blockDim.x) c_data[cs + p] = cacc[p];
+    return;
+  }
   for (int p = cs + threadIdx.x; p < ce; p += blockDim.x) c_data[p] = 0.f;
   __syncthreads();
-  const int as = a_indptr[row], ae = a_indptr[row + 1];
   for (int p = as + wave; p < ae; p += nwave) {
     const int k = a_indices[p];
     const float av = a_data[p];
@@ -226,8 +321,12 @@ bppsa_status bppsa_launch_spgemm_indices(const bppsa_csr& A, const bppsa_csr& B,
 
 bppsa_status bppsa_launch_spgemm_numeric(const bppsa_csr& A, const bppsa_csr& B, const int32_t* c_indptr,
                                          const int32_t* c_indices, float* c_data, hipStream_t stream) {
-  spgemm_numeric_kernel<<<A.rows, 256, 0, stream>>>(A.indptr, A.indices, A.data, B.indptr, B.indices, B.data,
-                                                    c_indptr, c_indices, c_data);
+  if (B.cols <= kNumericCap)
+    spgemm_numeric_kernel<true><<<A.rows, 256, 0, stream>>>(B.cols, A.indptr, A.indices, A.data, B.indptr, B.indices,
+                                                            B.data, c_indptr, c_indices, c_data);
+  else
+    spgemm_numeric_kernel<false><<<A.rows, 256, 0, stream>>>(B.cols, A.indptr, A.indices, A.data, B.indptr,
+                                                             B.indices, B.data, c_indptr, c_indices, c_data);
   BPPSA_CHECK_LAUNCH();
   return BPPSA_OK;
 }
