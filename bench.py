@@ -23,13 +23,13 @@ HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E bandwidth
 
 # HBM traffic of one scan_h20_kernel launch, from two `rocprofv3 --pmc` runs (FETCH_SIZE, then
 # WRITE_SIZE, KiB per dispatch), each scaled by what the same counter reads for the 768,000,000-byte
-# calibration copy (FETCH_SIZE reads 375,011.6 KiB for 750,000 KiB fetched: scale 2.000; WRITE_SIZE
-# reads 750,010.7 for 750,000 written: scale 1.000).  Offline figures: the counters cannot be read
+# calibration copy (FETCH_SIZE reads 375,011.5 KiB for 750,000 KiB fetched: scale 2.000; WRITE_SIZE
+# reads 750,008.4 for 750,000 written: scale 1.000).  Offline figures: the counters cannot be read
 # inside this process.  Keyed by (T, B, H); the summaries are the profiles/*.txt of the same workloads.
-PMC_COPY_SCALE = {"FETCH_SIZE": 750000.0 / 375011.5625, "WRITE_SIZE": 750000.0 / 750010.6875}
+PMC_COPY_SCALE = {"FETCH_SIZE": 750000.0 / 375011.5391, "WRITE_SIZE": 750000.0 / 750008.3906}
 PMC_SCAN_KIB = {
-    (1000, 16, 20): {"FETCH_SIZE": 13600.9792, "WRITE_SIZE": 2917.6104},
-    (30000, 16, 20): {"FETCH_SIZE": 402788.0385, "WRITE_SIZE": 113178.5168},
+    (1000, 16, 20): {"FETCH_SIZE": 13612.8356, "WRITE_SIZE": 2420.0404},
+    (30000, 16, 20): {"FETCH_SIZE": 402720.7596, "WRITE_SIZE": 72385.0481},
 }
 
 
@@ -105,6 +105,26 @@ def time_steps(bp, b, steps, warmup):
     parts = {name: statistics.mean(e[i].elapsed_time(e[i + 1]) for e in evs)
              for i, name in enumerate(("build_jacobians_ms", "scan_ms", "param_grads_ms"))}
     return wall_ms, parts
+
+
+def time_steps_cold(bp, b, steps):
+    """Per-step HIP-event time when a 1 GiB buffer is overwritten before every step, so that
+    neither the 256 MB memory-side cache nor the L2s hold any of the step's inputs."""
+    import torch
+    evict = torch.empty(1 << 28, dtype=torch.float32, device="cuda")
+    times = []
+    for i in range(steps):
+        evict.fill_(float(i))
+        a, z = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        bp.build_jacobians(bp.RNN_TANH, b["h"], w_hh=b["w_hh"], Jt=b["Jt"])
+        bp.scan(b["Jt"], b["seed"], G=b["G"], g0=None, workspace=b["scan_ws"])
+        bp.param_grads(bp.RNN_TANH, b["h"], b["x"], b["G"], out=b["out"], workspace=b["pg_ws"])
+        z.record()
+        torch.cuda.synchronize()
+        times.append(a.elapsed_time(z))
+    del evict
+    return statistics.median(times)
 
 
 def time_scan_only(bp, b, steps, warmup):
@@ -344,6 +364,7 @@ def main():
     bufs = prepare(bp, w)
     wall_ms, parts = time_steps(bp, bufs, args.steps, args.warmup)
 
+    cold_ms = time_steps_cold(bp, bufs, max(5, min(30, args.steps)))
     scan_bytes = scan_algorithmic_bytes(T, B, H)
     scan_gbps = scan_bytes / (parts["scan_ms"] * 1e-3) / 1e9
     out = {
@@ -362,6 +383,7 @@ def main():
         "config": {"workload": "rnn_tanh_H20_I1_T1000_B16 (configs[1])", "T": T, "B": B, "H": H,
                    "parallelism": "single-gpu"},
         "breakdown_ms": {k: round(v, 5) for k, v in parts.items()},
+        "cold_cache_step_ms": round(cold_ms, 5),
         "scan_gbps": round(scan_gbps, 2),
         "roofline": {"kernel": "bppsa_scan", "bound": "hbm", "achieved": round(scan_gbps, 2),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(scan_gbps / HBM_PEAK_GBPS, 5),
