@@ -394,6 +394,11 @@ def main():
         del bufs
         torch.cuda.empty_cache()
         out["long_scan"] = long_scan(bp, workloads, args.steps)
+        # the box's own streaming rate (768 MB read + 768 MB written), for context beside the 8 TB/s peak
+        cal = copy_calibration(bp, 10)
+        torch.cuda.empty_cache()
+        out["measured_copy_gbps"] = cal["gbps_read_plus_write"]
+        out["long_scan"]["frac_of_measured_copy"] = round(out["long_scan"]["gbps"] / cal["gbps_read_plus_write"], 5)
 
     if not args.no_cpu:
         ms, reps = cpu_baseline(w)

@@ -6,8 +6,14 @@
 // In place: a[0..n) holds row lengths on entry, the exclusive prefix sum on exit; a[n] = total.
 bppsa_status bppsa_lengths_to_indptr(int32_t* a, int n, hipStream_t stream);
 
-// y = A x.
-bppsa_status bppsa_launch_spmv(const bppsa_csr& A, const float* x, float* y, hipStream_t stream);
+// y = A x.  With a diagonal D given by its values d (one per row of A), y2 = D y is written
+// as well: the product with a diagonal matrix that follows in a chain costs no launch.
+bppsa_status bppsa_launch_spmv(const bppsa_csr& A, const float* x, float* y, hipStream_t stream,
+                               const float* d = nullptr, float* y2 = nullptr);
+
+// *flag (device int, preset to 1 by the caller) is cleared if A is not square with exactly the
+// entries (i, i), i.e. indptr[i] = i and indices[i] = i.
+bppsa_status bppsa_launch_check_diagonal(const bppsa_csr& A, int* flag, hipStream_t stream);
 
 // Structural product C = A B.
 // Pass 1 writes the length of every row of C into c_indptr[0..rows) and adds the number of

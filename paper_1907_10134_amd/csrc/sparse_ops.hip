@@ -47,7 +47,8 @@ lengths_to_indptr_kernel(int32_t* __restrict__ a, int n) {
 // One wave per row: lanes stride over the row's entries, then reduce.
 __global__ void __launch_bounds__(256)
 spmv_wave_kernel(int rows, const int32_t* __restrict__ indptr, const int32_t* __restrict__ indices,
-                 const float* __restrict__ data, const float* __restrict__ x, float* __restrict__ y) {
+                 const float* __restrict__ data, const float* __restrict__ x, float* __restrict__ y,
+                 const float* __restrict__ d, float* __restrict__ y2) {
   const int lane = threadIdx.x & 63;
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= rows) return;
@@ -55,19 +56,34 @@ spmv_wave_kernel(int rows, const int32_t* __restrict__ indptr, const int32_t* __
   float acc = 0.f;
   for (int p = s + lane; p < e; p += 64) acc += data[p] * x[indices[p]];
   for (int m = 32; m >= 1; m >>= 1) acc += __shfl_xor(acc, m);
-  if (lane == 0) y[row] = acc;
+  if (lane == 0) {
+    y[row] = acc;
+    if (y2) y2[row] = d[row] * acc;
+  }
 }
 
 // One lane per row: for matrices with about one entry per row (ReLU, max-pooling).
 __global__ void __launch_bounds__(256)
 spmv_lane_kernel(int rows, const int32_t* __restrict__ indptr, const int32_t* __restrict__ indices,
-                 const float* __restrict__ data, const float* __restrict__ x, float* __restrict__ y) {
+                 const float* __restrict__ data, const float* __restrict__ x, float* __restrict__ y,
+                 const float* __restrict__ d, float* __restrict__ y2) {
   const int row = blockIdx.x * blockDim.x + threadIdx.x;
   if (row >= rows) return;
   const int s = indptr[row], e = indptr[row + 1];
   float acc = 0.f;
   for (int p = s; p < e; ++p) acc += data[p] * x[indices[p]];
   y[row] = acc;
+  if (y2) y2[row] = d[row] * acc;
+}
+
+__global__ void __launch_bounds__(256)
+check_diagonal_kernel(int rows, const int32_t* __restrict__ indptr, const int32_t* __restrict__ indices,
+                      int* __restrict__ flag) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i > rows) return;
+  bool ok = indptr[i] == i;
+  if (i < rows) ok = ok && indices[i] == i;
+  if (!ok) *flag = 0;
 }
 
 // Mark, in an LDS bitmap, every column of B reachable from row `row` of A.  Waves take
@@ -279,12 +295,22 @@ bppsa_status bppsa_lengths_to_indptr(int32_t* a, int n, hipStream_t stream) {
   return BPPSA_OK;
 }
 
-bppsa_status bppsa_launch_spmv(const bppsa_csr& A, const float* x, float* y, hipStream_t stream) {
+bppsa_status bppsa_launch_spmv(const bppsa_csr& A, const float* x, float* y, hipStream_t stream,
+                               const float* d, float* y2) {
   if (A.rows < 1) return BPPSA_OK;
   if (A.nnz >= 4 * (int64_t)A.rows)
-    spmv_wave_kernel<<<bppsa_ceil_div(A.rows, 4), 256, 0, stream>>>(A.rows, A.indptr, A.indices, A.data, x, y);
+    spmv_wave_kernel<<<bppsa_ceil_div(A.rows, 4), 256, 0, stream>>>(A.rows, A.indptr, A.indices, A.data, x, y, d,
+                                                                    y2);
   else
-    spmv_lane_kernel<<<bppsa_ceil_div(A.rows, 256), 256, 0, stream>>>(A.rows, A.indptr, A.indices, A.data, x, y);
+    spmv_lane_kernel<<<bppsa_ceil_div(A.rows, 256), 256, 0, stream>>>(A.rows, A.indptr, A.indices, A.data, x, y,
+                                                                      d, y2);
+  BPPSA_CHECK_LAUNCH();
+  return BPPSA_OK;
+}
+
+bppsa_status bppsa_launch_check_diagonal(const bppsa_csr& A, int* flag, hipStream_t stream) {
+  if (A.rows != A.cols || A.nnz != A.rows) return BPPSA_EINVAL;
+  check_diagonal_kernel<<<bppsa_ceil_div(A.rows + 1, 256), 256, 0, stream>>>(A.rows, A.indptr, A.indices, flag);
   BPPSA_CHECK_LAUNCH();
   return BPPSA_OK;
 }

@@ -47,6 +47,7 @@ struct Op {
   int vin, vout;          // kSpmv
   bool live;
   bool tail;              // the optional inclusive-tail product
+  bool diag = false;      // kSpmv whose matrix has exactly the entries (i, i): fused into its producer
 };
 
 int ceil_log2(int v) {
@@ -273,6 +274,24 @@ extern "C" bppsa_status bppsa_spscan_plan_create(int n, const bppsa_csr* Jt, int
     P.mm_flops += 2 * pr.madds;
     P.live_product_ids.push_back((int)i);
   }
+  // Input matrices with the pattern of the identity (the ReLU Jacobians of Appendix D.2) are
+  // recognised once, here, so that a run can apply them inside the kernel that produces
+  // their operand.
+  int* d_flag = static_cast<int*>(ar.take(sizeof(int)));
+  if (!d_flag && st == BPPSA_OK) st = BPPSA_EWORKSPACE;
+  for (size_t i = 0; i < P.ops.size() && st == BPPSA_OK; ++i) {
+    Op& op = P.ops[i];
+    if (!op.live || op.kind != kSpmv || op.mat >= n) continue;
+    const bppsa_csr& A = Jt[op.mat];
+    if (A.rows != A.cols || A.nnz != A.rows) continue;
+    int flag = 1;
+    if (hipMemcpyAsync(d_flag, &flag, sizeof(int), hipMemcpyHostToDevice, s) != hipSuccess) { st = BPPSA_EHIP; break; }
+    st = bppsa_launch_check_diagonal(A, d_flag, s);
+    if (st != BPPSA_OK) break;
+    if (hipMemcpyAsync(&flag, d_flag, sizeof(int), hipMemcpyDeviceToHost, s) != hipSuccess ||
+        hipStreamSynchronize(s) != hipSuccess) { st = BPPSA_EHIP; break; }
+    op.diag = flag != 0;
+  }
   if (st == BPPSA_OK && hipStreamSynchronize(s) != hipSuccess) st = BPPSA_EHIP;
   if (st != BPPSA_OK) { delete plan; return st; }
   for (const Op& op : P.ops) {
@@ -337,7 +356,8 @@ extern "C" bppsa_status bppsa_spscan_run(const bppsa_spscan_plan* plan, const bp
     if (v.grad_index >= 0 && grads[v.grad_index]) return grads[v.grad_index];
     return v.buf;
   };
-  for (const Op& op : P.ops) {
+  for (size_t i = 0; i < P.ops.size(); ++i) {
+    const Op& op = P.ops[i];
     if (!op.live) continue;
     bppsa_status st;
     if (op.kind == kSpgemm) {
@@ -346,7 +366,18 @@ extern "C" bppsa_status bppsa_spscan_run(const bppsa_spscan_plan* plan, const bp
                                        pr.indptr, pr.indices, pr.data, s);
     } else {
       if (op.tail && !grads[P.n - 1]) continue;     // inclusive tail not requested
-      st = bppsa_launch_spmv(mat_desc(P, Jt, op.mat), vec_ptr(op.vin), vec_ptr(op.vout), s);
+      // a diagonal matrix that consumes this product is applied in the same launch
+      size_t j = i + 1;
+      while (j < P.ops.size() && !P.ops[j].live) ++j;
+      const bool fuse = j < P.ops.size() && P.ops[j].kind == kSpmv && P.ops[j].diag &&
+                        P.ops[j].vin == op.vout && !(P.ops[j].tail && !grads[P.n - 1]);
+      if (fuse) {
+        st = bppsa_launch_spmv(mat_desc(P, Jt, op.mat), vec_ptr(op.vin), vec_ptr(op.vout), s,
+                               Jt[P.ops[j].mat].data, vec_ptr(P.ops[j].vout));
+        i = j;                                      // the diagonal step is done
+      } else {
+        st = bppsa_launch_spmv(mat_desc(P, Jt, op.mat), vec_ptr(op.vin), vec_ptr(op.vout), s);
+      }
     }
     if (st != BPPSA_OK) return st;
   }
