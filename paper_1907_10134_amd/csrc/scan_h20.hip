@@ -219,7 +219,7 @@ __device__ __forceinline__ void fetch2(const float* src, float& a, float& b) {
 }
 __device__ __forceinline__ void wait_all_memory_ops() { __builtin_amdgcn_s_waitcnt(0); }
 
-// Look-back, run by wave 0.  Leaves the vector entering this segment in vin[0..20).
+// Look-back, run by one wave.  Leaves the vector entering this segment in vin[0..20).
 // Window: the 64 predecessors k-1 .. k-64 of the same sample; status words are stored
 // sample-major so that the window is 256 contiguous bytes (two cache lines per poll).  The nearest one that has
 // published its inclusive vector is the base; every nearer one must have published its
@@ -378,11 +378,18 @@ __device__ __forceinline__ void drain_queue(int qid, int T, int B, int n, int ns
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, slot = lane >> 2, q = lane & 3;
     if (tid == 0) *sh.ticket_s = __hip_atomic_fetch_add(&hdr->ticket[qid][0], 1, __ATOMIC_RELAXED, SCOPE);
     __syncthreads();
-    const int ticket = *sh.ticket_s;
+    const int ticket = __builtin_amdgcn_readfirstlane(*sh.ticket_s);
     if (ticket >= quota) break;                  // uniform: the queue is empty
     const int k = ticket / bq;                   // segment, 0 = seed end
     const int b = qid + nq * (ticket - k * bq);
     const size_t me = (size_t)k * B + b;
+    // The four waves have different amounts of work (below); which wave takes which part
+    // rotates with the ticket, so that the workgroups sharing a compute unit do not all put
+    // their heaviest wave on the same SIMD.
+    //   role 0: 9 of the 25 level-0 blocks;  role 1: 6 blocks and level 4;
+    //   role 2: 6 blocks, a level-3 product and the top of the down-sweep;
+    //   role 3: 4 blocks, a level-3 product and the look-back.
+    const int role = (wave + ticket) & 3;
     BPPSA_STAMP(0);
     const int c0 = k * S;                        // first chain element of the segment
     const int m = (n - c0 < S) ? (n - c0) : S;   // real elements; the rest are identity tiles
@@ -419,14 +426,14 @@ __device__ __forceinline__ void drain_queue(int qid, int T, int B, int n, int ns
       v4f acc[9];
       float* A = mat + (2 * slot + 1) * TS;
       const float* Bm = mat + (2 * slot) * TS;
-      switch (wave) {
+      switch (role) {
         case 0: level0_compute<0, 3, 0, 3>(A, Bm, q, acc); break;
         case 1: level0_compute<0, 3, 3, 2>(A, Bm, q, acc); break;
         case 2: level0_compute<3, 2, 0, 3>(A, Bm, q, acc); break;
         default: level0_compute<3, 2, 3, 2>(A, Bm, q, acc); break;
       }
       __syncthreads();
-      switch (wave) {
+      switch (role) {
         case 0: level0_store<0, 3, 0, 3>(A, q, acc); break;
         case 1: level0_store<0, 3, 3, 2>(A, q, acc); break;
         case 2: level0_store<3, 2, 0, 3>(A, q, acc); break;
@@ -434,16 +441,22 @@ __device__ __forceinline__ void drain_queue(int qid, int T, int B, int n, int ns
       }
     }
     __syncthreads();
+    BPPSA_STAMP(11);
     // ---- up-sweep levels 1..4: pairs (l, r) = (i + 2^d - 1, i + 2^(d+1) - 1) ------------
-#pragma unroll
-    for (int d = 1; d < 5; ++d) {
-      const int npairs = S >> (d + 1);
-      for (int pr = wave; pr < npairs; pr += 4) {
-        const int i = pr << (d + 1);
-        wave_product(mat + (i + (2 << d) - 1) * TS, mat + (i + (1 << d) - 1) * TS, slot, q);
-      }
-      __syncthreads();
+    // Levels 1 and 2 of the eight tiles 8w .. 8w+7 belong to the wave of role w alone: the LDS operations
+    // of one wave complete in order, so no workgroup barrier is needed between the two.
+    {
+      float* sub = mat + 8 * role * TS;
+      wave_product(sub + 3 * TS, sub + 1 * TS, slot, q);
+      wave_product(sub + 7 * TS, sub + 5 * TS, slot, q);
+      wave_product(sub + 7 * TS, sub + 3 * TS, slot, q);
     }
+    __syncthreads();
+    BPPSA_STAMP(12);
+    if (role >= 2) wave_product(mat + (16 * (role - 2) + 15) * TS, mat + (16 * (role - 2) + 7) * TS, slot, q);
+    __syncthreads();
+    if (role == 1) wave_product(mat + 31 * TS, mat + 15 * TS, slot, q);
+    __syncthreads();
     BPPSA_STAMP(2);
     float* total = mat + (S - 1) * TS;
 
@@ -458,7 +471,7 @@ __device__ __forceinline__ void drain_queue(int qid, int T, int B, int n, int ns
 
     BPPSA_STAMP(3);
     // ---- incoming vector, inclusive vector -----------------------------------------------
-    if (wave == 0) {
+    if (role == 3) {
       if (k == 0) {
         if (lane < H) vin[lane] = seed[(size_t)b * H + lane];
       } else {
@@ -488,8 +501,46 @@ __device__ __forceinline__ void drain_queue(int qid, int T, int B, int n, int ns
     // ---- down-sweep: T <- a[l]; a[l] <- a[r]; a[r] <- T a[r] ----------------------------
     if (tid < H) vec[(S - 1) * H + tid] = vin[tid];
     __syncthreads();
+    // Levels 4, 3 and 2 (1, 2 and 4 pairs) are run by one wave alone, again without workgroup
+    // barriers: every lane's reads of a level are issued before any lane's writes.
+    if (role == 2) {
 #pragma unroll
-    for (int d = 4; d >= 0; --d) {
+      for (int d = 4; d >= 2; --d) {
+        const int npairs = S >> (d + 1);
+        float res[2], keep[2];
+#pragma unroll
+        for (int r = 0; r < 2; ++r) {
+          const int e = lane + 64 * r;
+          res[r] = 0.f;
+          keep[r] = 0.f;
+          if (e < npairs * H) {
+            const int pr = e / H, row = e - pr * H;
+            const int i = pr << (d + 1);
+            const int l = i + (1 << d) - 1, rr = i + (2 << d) - 1;
+            res[r] = row_dot(mat + l * TS, row, vec + rr * H);
+            keep[r] = vec[rr * H + row];
+          }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int r = 0; r < 2; ++r) {
+          const int e = lane + 64 * r;
+          if (e < npairs * H) {
+            const int pr = e / H, row = e - pr * H;
+            const int i = pr << (d + 1);
+            const int l = i + (1 << d) - 1, rr = i + (2 << d) - 1;
+            vec[l * H + row] = keep[r];
+            vec[rr * H + row] = res[r];
+          }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __builtin_amdgcn_wave_barrier();
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int d = 1; d >= 0; --d) {
       const int npairs = S >> (d + 1);
       float res[2];
       float keep[2];
