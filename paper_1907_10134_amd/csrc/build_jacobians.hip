@@ -58,6 +58,7 @@ constexpr int kH20TilesPerPass = 5;
 
 typedef float bj_v4f __attribute__((ext_vector_type(4)));
 
+template <bool STREAM>
 __global__ void __launch_bounds__(kH20Threads)
 rnn_jacobians_h20_kernel(int tiles, int B, const float* __restrict__ h, const float* __restrict__ w_hh,
                          float* __restrict__ Jt) {
@@ -73,7 +74,9 @@ rnn_jacobians_h20_kernel(int tiles, int B, const float* __restrict__ h, const fl
   for (int m = blockIdx.x * kH20TilesPerPass + slot; m < tiles; m += step) {
     const bj_v4f hv = *reinterpret_cast<const bj_v4f*>(h + (size_t)(m + B) * H + j4);   // h[t+1][b][j4..]
     const bj_v4f o = w * (1.0f - hv * hv);
-    __builtin_nontemporal_store(o, reinterpret_cast<bj_v4f*>(Jt + (size_t)m * H * H + p * 4));
+    bj_v4f* dst = reinterpret_cast<bj_v4f*>(Jt + (size_t)m * H * H + p * 4);
+    if (STREAM) __builtin_nontemporal_store(o, dst);   // far larger than the caches: do not allocate
+    else *dst = o;                                     // small enough to be read back from cache
   }
 }
 
@@ -104,7 +107,10 @@ extern "C" bppsa_status bppsa_build_jacobians(int cell, int T, int B, int H, int
     const int tiles = T * B;
     int grid = bppsa_ceil_div(tiles, kH20TilesPerPass);
     if (grid > 512) grid = 512;
-    rnn_jacobians_h20_kernel<<<grid, kH20Threads, 0, s>>>(tiles, B, h, w_hh, Jt);
+    if ((size_t)tiles * 1600 > ((size_t)128 << 20))
+      rnn_jacobians_h20_kernel<true><<<grid, kH20Threads, 0, s>>>(tiles, B, h, w_hh, Jt);
+    else
+      rnn_jacobians_h20_kernel<false><<<grid, kH20Threads, 0, s>>>(tiles, B, h, w_hh, Jt);
     BPPSA_CHECK_LAUNCH();
     return BPPSA_OK;
   }

@@ -574,9 +574,14 @@ __device__ __forceinline__ void drain_queue(int qid, int T, int B, int n, int ns
 
     BPPSA_STAMP(5);
     // ---- store: the vector entering element p is g[T-c0-p] = G[T-1-c0-p] ------------------
+    // gradients of a long sequence are streamed past the caches; a short one is left in cache
+    // for the parameter-gradient pass that follows
+    const bool stream_out = (size_t)T * B * H * sizeof(float) > ((size_t)64 << 20);
     for (int e = tid; e < m * H; e += kThreads) {
       const int p = e / H, row = e - p * H;
-      __builtin_nontemporal_store(vec[e], G + ((size_t)(T - 1 - c0 - p) * B + b) * H + row);
+      float* dst = G + ((size_t)(T - 1 - c0 - p) * B + b) * H + row;
+      if (stream_out) __builtin_nontemporal_store(vec[e], dst);
+      else *dst = vec[e];
     }
     BPPSA_STAMP(6);
     __syncthreads();                              // LDS and ticket_s are reused by the next segment
