@@ -107,6 +107,31 @@ def time_steps(bp, b, steps, warmup):
     return wall_ms, parts
 
 
+def time_fused(bp, b, steps, warmup):
+    """The tanh-RNN path without materialised Jacobians: bppsa_rnn_scan_fused + bppsa_param_grads."""
+    import torch
+
+    def step():
+        bp.rnn_scan_fused(b["h"], b["w_hh"], b["seed"], G=b["G"], g0=None, workspace=b["scan_ws"])
+        bp.param_grads(bp.RNN_TANH, b["h"], b["x"], b["G"], out=b["out"], workspace=b["pg_ws"])
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    for a, z in evs:
+        a.record()
+        bp.rnn_scan_fused(b["h"], b["w_hh"], b["seed"], G=b["G"], g0=None, workspace=b["scan_ws"])
+        z.record()
+    torch.cuda.synchronize()
+    return wall_ms, statistics.mean(a.elapsed_time(z) for a, z in evs)
+
+
 def time_steps_cold(bp, b, steps):
     """Per-step HIP-event time when a 1 GiB buffer is overwritten before every step, so that
     neither the 256 MB memory-side cache nor the L2s hold any of the step's inputs."""
@@ -146,12 +171,14 @@ def long_scan(bp, workloads, steps):
     b2 = prepare(bp, w2)
     bp.build_jacobians(bp.RNN_TANH, b2["h"], w_hh=b2["w_hh"], Jt=b2["Jt"])
     ms = time_scan_only(bp, b2, steps=max(5, min(50, steps)), warmup=3)
+    _, fused_ms = time_fused(bp, b2, max(5, min(50, steps)), 3)
     nbytes = scan_algorithmic_bytes(w2["T"], w2["B"], w2["H"])
     gbps = nbytes / (ms * 1e-3) / 1e9
     return {"workload": "rnn_tanh_H20_I1_T30000_B16 (configs[2])", "scan_ms": round(ms, 5),
             "algorithmic_bytes": nbytes, "gbps": round(gbps, 2),
             "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 5),
-            "traffic": measured_traffic_bytes(w2["T"], w2["B"], w2["H"])}
+            "traffic": measured_traffic_bytes(w2["T"], w2["B"], w2["H"]),
+            "fused_scan_ms": round(fused_ms, 5)}
 
 
 def copy_calibration(bp, steps):
@@ -365,6 +392,7 @@ def main():
     wall_ms, parts = time_steps(bp, bufs, args.steps, args.warmup)
 
     cold_ms = time_steps_cold(bp, bufs, max(5, min(30, args.steps)))
+    fused_wall_ms, fused_scan_ms = time_fused(bp, bufs, args.steps, args.warmup)
     scan_bytes = scan_algorithmic_bytes(T, B, H)
     scan_gbps = scan_bytes / (parts["scan_ms"] * 1e-3) / 1e9
     out = {
@@ -384,6 +412,9 @@ def main():
                    "parallelism": "single-gpu"},
         "breakdown_ms": {k: round(v, 5) for k, v in parts.items()},
         "cold_cache_step_ms": round(cold_ms, 5),
+        "fused_path": {"what": "bppsa_rnn_scan_fused + bppsa_param_grads (Jacobians generated inside the scan, "
+                               "never stored); not the metric above", "step_ms": round(fused_wall_ms, 5),
+                       "scan_ms": round(fused_scan_ms, 5)},
         "scan_gbps": round(scan_gbps, 2),
         "roofline": {"kernel": "bppsa_scan", "bound": "hbm", "achieved": round(scan_gbps, 2),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(scan_gbps / HBM_PEAK_GBPS, 5),

@@ -129,6 +129,19 @@ bppsa_status bppsa_scan(int T, int B, int H,
                         float* G, float* g0,
                         void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * bppsa_build_jacobians + bppsa_scan in one pass for the tanh RNN: the transposed
+ * Jacobians of Section 4.1, Jt[t][i][j] = W_hh[j][i] (1 - h[t+1][j]^2), are generated
+ * inside the scan kernel from h [T+1,B,H] and w_hh [H,H] and never stored, so neither
+ * the [T,B,H,H] array nor its HBM round trip exists.  Outputs, g0 and the workspace
+ * (bppsa_scan_workspace_bytes) are those of bppsa_scan, and the values are bit-identical
+ * to bppsa_build_jacobians followed by bppsa_scan.  H = 20 only (the paper's RNN size):
+ * other sizes return BPPSA_EUNSUPPORTED and should use the two calls.
+ */
+bppsa_status bppsa_rnn_scan_fused(int T, int B, int H, const float* h, const float* w_hh,
+                                  const float* seed, float* G, float* g0,
+                                  void* workspace, size_t workspace_bytes, void* stream);
+
 /* Bytes of workspace bppsa_param_grads needs (host-only, pure). */
 size_t bppsa_param_grads_workspace_bytes(int cell, int T, int B, int H, int I);
 

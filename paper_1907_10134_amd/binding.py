@@ -44,6 +44,8 @@ def _load():
     lib.bppsa_scan_workspace_bytes.argtypes = [c_int] * 3
     lib.bppsa_scan.restype = c_int
     lib.bppsa_scan.argtypes = [c_int] * 3 + [c_void_p] * 5 + [c_size_t, c_void_p]
+    lib.bppsa_rnn_scan_fused.restype = c_int
+    lib.bppsa_rnn_scan_fused.argtypes = [c_int] * 3 + [c_void_p] * 6 + [c_size_t, c_void_p]
     lib.bppsa_param_grads_workspace_bytes.restype = c_size_t
     lib.bppsa_param_grads_workspace_bytes.argtypes = [c_int] * 5
     lib.bppsa_param_grads.restype = c_int
@@ -182,6 +184,21 @@ def scan(Jt, seed, G=None, g0=None, workspace=None, stream=None):
     _check(_lib.bppsa_scan(T, B, H, _ptr(Jt), _ptr(seed), _ptr(G), _ptr(g0),
                            workspace.data_ptr(), workspace.numel() * workspace.element_size(),
                            _stream(stream)), "bppsa_scan")
+    return G
+
+
+def rnn_scan_fused(h, w_hh, seed, G=None, g0=None, workspace=None, stream=None):
+    """bppsa_rnn_scan_fused: the tanh-RNN scan with the Jacobians generated in the kernel."""
+    T1, B, H = h.shape
+    T = T1 - 1
+    if G is None:
+        G = torch.empty((T, B, H), dtype=torch.float32, device=h.device)
+    if workspace is None:
+        workspace = _workspace(scan_workspace_bytes(T, B, H), h.device)
+    _check(_lib.bppsa_rnn_scan_fused(T, B, H, _ptr(h, name="h"), _ptr(w_hh, name="w_hh"), _ptr(seed, name="seed"),
+                                     _ptr(G, name="G"), _ptr(g0),
+                                     workspace.data_ptr(), workspace.numel(), _stream(stream)),
+           "bppsa_rnn_scan_fused")
     return G
 
 

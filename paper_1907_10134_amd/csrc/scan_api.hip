@@ -38,3 +38,19 @@ extern "C" bppsa_status bppsa_scan(int T, int B, int H,
   if (H == 20) return bppsa_scan_h20(T, B, Jt, seed, G, g0, workspace, (hipStream_t)stream);
   return bppsa_scan_generic(T, B, H, Jt, seed, G, g0, workspace, (hipStream_t)stream);
 }
+
+extern "C" bppsa_status bppsa_rnn_scan_fused(int T, int B, int H, const float* h, const float* w_hh,
+                                             const float* seed, float* G, float* g0, void* workspace,
+                                             size_t workspace_bytes, void* stream) {
+  if (T < 1 || B < 1 || H < 1) return BPPSA_EINVAL;
+  if (!h || !w_hh || !seed || !G) return BPPSA_EINVAL;
+  if (bppsa_mul_overflows(T, B, H, H)) return BPPSA_EOVERFLOW;
+  if (H != 20) return BPPSA_EUNSUPPORTED;        // the single-pass kernel exists for this size only
+  const size_t need = scan_ws_bytes(T, B, H);
+  if (!workspace || workspace_bytes < need) return BPPSA_EWORKSPACE;
+  if ((uintptr_t)workspace & 255) return BPPSA_EINVAL;
+  if (T == 1 && !g0) {                           // G[0] = seed, nothing to multiply
+    return bppsa_scan_generic(T, B, H, nullptr, seed, G, g0, workspace, (hipStream_t)stream);
+  }
+  return bppsa_scan_h20(T, B, nullptr, seed, G, g0, workspace, (hipStream_t)stream, h, w_hh);
+}

@@ -362,7 +362,8 @@ template <int SCOPE>
 __device__ __forceinline__ void drain_queue(int qid, int T, int B, int n, int nseg, int nq,
                                             const float* __restrict__ Jt, const float* __restrict__ seed,
                                             float* __restrict__ G, float* __restrict__ g0, Header* hdr,
-                                            int* status, float* agg, float* incl, const Shared sh
+                                            int* status, float* agg, float* incl, const Shared sh,
+                                            const float* __restrict__ hsrc, const float* __restrict__ wt
                                             BPPSA_TRACE_PARAM) {
   float* const mat = sh.mat;
   float* const vec = sh.vec;
@@ -403,8 +404,18 @@ __device__ __forceinline__ void drain_queue(int qid, int T, int B, int n, int ns
         const int e = tid + r * kThreads;
         const int p = e / (HH / 4), off = e - p * (HH / 4);
         if (e < kChunks && p < m) {
-          const float* src = Jt + ((size_t)(T - 1 - c0 - p) * B + b) * HH;
-          tmp[r] = reinterpret_cast<const v4f*>(src)[off];
+          if (hsrc) {
+            // fused tanh-RNN form (Section 4.1): the tile of step t = T-1-c0-p is generated from
+            // h[t+1] and the transposed weights, Jt[i][j] = W_hh[j][i] (1 - h[t+1][j]^2), instead
+            // of being read
+            const int i = off / 5, j4 = (off - i * 5) * 4;
+            const v4f wv = *reinterpret_cast<const v4f*>(wt + i * H + j4);
+            const v4f hv = *reinterpret_cast<const v4f*>(hsrc + ((size_t)(T - c0 - p) * B + b) * H + j4);
+            tmp[r] = wv * (1.0f - hv * hv);
+          } else {
+            const float* src = Jt + ((size_t)(T - 1 - c0 - p) * B + b) * HH;
+            tmp[r] = reinterpret_cast<const v4f*>(src)[off];
+          }
         } else {
           const int i0 = (off * 4) / H, j0 = off * 4 - i0 * H;   // identity padding
           tmp[r] = v4f{i0 == j0 ? 1.f : 0.f, i0 == j0 + 1 ? 1.f : 0.f, i0 == j0 + 2 ? 1.f : 0.f,
@@ -592,7 +603,8 @@ template <bool LOCAL>
 __global__ void __launch_bounds__(kThreads, 3)
 scan_h20_kernel(int T, int B, int n, int nseg, int nq, int skip_dies, const float* __restrict__ Jt,
                 const float* __restrict__ seed, float* __restrict__ G, float* __restrict__ g0,
-                Header* hdr, int* status, float* agg, float* incl BPPSA_TRACE_PARAM) {
+                Header* hdr, int* status, float* agg, float* incl, const float* __restrict__ hsrc,
+                const float* __restrict__ wt BPPSA_TRACE_PARAM) {
   // 32 tiles, then room so that the 32 down-sweep vectors can start on top of the last tile
   // (the segment total, dead once the inclusive vector has been formed)
   __shared__ __attribute__((aligned(16))) float lds[(S - 1) * TS + S * H];
@@ -601,8 +613,8 @@ scan_h20_kernel(int T, int B, int n, int nseg, int nq, int skip_dies, const floa
   const Shared sh = {lds, lds + (S - 1) * TS, vin, &ticket_s};
   if (!LOCAL) {
     const int qid = (int)(blockIdx.x % (unsigned)nq);
-    drain_queue<__HIP_MEMORY_SCOPE_AGENT>(qid, T, B, n, nseg, nq, Jt, seed, G, g0, hdr, status, agg, incl, sh
-                                          BPPSA_TRACE_FWD);
+    drain_queue<__HIP_MEMORY_SCOPE_AGENT>(qid, T, B, n, nseg, nq, Jt, seed, G, g0, hdr, status, agg, incl, sh,
+                                          hsrc, wt BPPSA_TRACE_FWD);
     return;
   }
   const int qid = xcc_id() & (kMaxQueues - 1);
@@ -614,8 +626,8 @@ scan_h20_kernel(int T, int B, int n, int nseg, int nq, int skip_dies, const floa
   if (threadIdx.x == 0)
     __hip_atomic_fetch_add(&hdr->started[aside ? kMaxQueues : qid][0], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   if (!aside)
-    drain_queue<__HIP_MEMORY_SCOPE_WORKGROUP>(qid, T, B, n, nseg, nq, Jt, seed, G, g0, hdr, status, agg, incl, sh
-                                              BPPSA_TRACE_FWD);
+    drain_queue<__HIP_MEMORY_SCOPE_WORKGROUP>(qid, T, B, n, nseg, nq, Jt, seed, G, g0, hdr, status, agg, incl, sh,
+                                              hsrc, wt BPPSA_TRACE_FWD);
   // A queue whose die received no workgroup is untouched.  That is certain only once every
   // workgroup of the grid has started; the workgroups that find this to be the case when they
   // run out of work (the last one to finish always does, because every workgroup waits for its
@@ -637,14 +649,19 @@ scan_h20_kernel(int T, int B, int n, int nseg, int nq, int skip_dies, const floa
   __syncthreads();
   for (int q = 0; q < kMaxQueues; ++q) {
     if ((unserved >> q) & 1)
-      drain_queue<__HIP_MEMORY_SCOPE_AGENT>(q, T, B, n, nseg, nq, Jt, seed, G, g0, hdr, status, agg, incl, sh
-                                            BPPSA_TRACE_FWD);
+      drain_queue<__HIP_MEMORY_SCOPE_AGENT>(q, T, B, n, nseg, nq, Jt, seed, G, g0, hdr, status, agg, incl, sh,
+                                            hsrc, wt BPPSA_TRACE_FWD);
   }
 }
 
-__global__ void clear_kernel(int* p, long long nwords) {
+// Zeroes the header and the status words; for the fused form also writes wt[i][j] = W_hh[j][i].
+__global__ void clear_kernel(int* p, long long nwords, const float* __restrict__ w_hh, float* __restrict__ wt) {
   const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < nwords) p[i] = 0;
+  if (w_hh && i < HH) {
+    const int r = (int)i / H, c = (int)i - r * H;
+    wt[c * H + r] = w_hh[i];
+  }
 }
 
 int resident_workgroups() {
@@ -662,10 +679,12 @@ int resident_workgroups() {
 
 }  // namespace
 
+// Jt given: the scan proper.  Jt == nullptr: the fused tanh-RNN form, tiles generated from
+// (h, w_hh) inside the kernel.
 bppsa_status bppsa_scan_h20(int T, int B, const float* Jt, const float* seed, float* G, float* g0,
-                            void* workspace, hipStream_t stream) {
+                            void* workspace, hipStream_t stream, const float* h, const float* w_hh) {
   const int n = g0 ? T : T - 1;                 // chain elements Jt[T-1] .. Jt[T-n]
-  if (n <= 0) {                                 // T == 1 without g0: only G[0] = seed
+  if (n <= 0) {                                 // T == 1 without g0: only G[0] = seed (no Jacobian is read)
     return bppsa_scan_generic(T, B, H, Jt, seed, G, g0, workspace, stream);
   }
   const int nseg = bppsa_ceil_div(n, S);
@@ -677,8 +696,10 @@ bppsa_status bppsa_scan_h20(int T, int B, const float* Jt, const float* seed, fl
   const size_t status_bytes = bppsa_align_up((size_t)nblk * sizeof(int), 256);
   float* agg = reinterpret_cast<float*>(ws + kHeaderBytes + status_bytes);
   float* incl = agg + (size_t)nblk * kAggStride;
+  float* wt = incl + (size_t)nblk * kIncStride;  // [H][H], fused form only
   const long long nwords = (kHeaderBytes + (long long)status_bytes) / 4;
-  clear_kernel<<<(int)((nwords + 255) / 256), 256, 0, stream>>>(reinterpret_cast<int*>(ws), nwords);
+  clear_kernel<<<(int)((nwords + 255) / 256), 256, 0, stream>>>(reinterpret_cast<int*>(ws), nwords, Jt ? nullptr : w_hh,
+                                                                wt);
   BPPSA_CHECK_LAUNCH();
   // Persistent grid: as many workgroups as the device holds at once (3 per compute unit).
   // BPPSA_H20_SKIP_DIES (a bit mask, tests only) makes the workgroups of the named dies stand
@@ -691,10 +712,10 @@ bppsa_status bppsa_scan_h20(int T, int B, const float* Jt, const float* seed, fl
   const int grid = (int)want;
   if (B % kMaxQueues == 0) {
     scan_h20_kernel<true><<<grid, kThreads, 0, stream>>>(T, B, n, nseg, kMaxQueues, skip_dies, Jt, seed, G, g0, hdr,
-                                                         status, agg, incl BPPSA_TRACE_ARG);
+                                                         status, agg, incl, Jt ? nullptr : h, wt BPPSA_TRACE_ARG);
   } else {
     scan_h20_kernel<false><<<grid, kThreads, 0, stream>>>(T, B, n, nseg, 1, 0, Jt, seed, G, g0, hdr, status,
-                                                          agg, incl BPPSA_TRACE_ARG);
+                                                          agg, incl, Jt ? nullptr : h, wt BPPSA_TRACE_ARG);
   }
   BPPSA_CHECK_LAUNCH();
   return BPPSA_OK;

@@ -34,15 +34,16 @@ static inline size_t bppsa_generic_scan_ws(int T, int B, int H, int want_g0) {
 #define BPPSA_H20_HEADER_BYTES 4096
 
 // Workspace of the single-pass scan: header, one status word, one published total and one
-// published inclusive vector per (segment, sample).
+// published inclusive vector per (segment, sample), and the transposed weights of the fused form.
 static inline size_t bppsa_h20_scan_ws(int T, int B) {
   const size_t nblk = (size_t)bppsa_ceil_div(T, BPPSA_H20_SEGMENT) * B;
   return BPPSA_H20_HEADER_BYTES + bppsa_align_up(nblk * sizeof(int), 256) +
-         nblk * (BPPSA_H20_AGG_STRIDE + BPPSA_H20_INC_STRIDE) * sizeof(float);
+         nblk * (BPPSA_H20_AGG_STRIDE + BPPSA_H20_INC_STRIDE) * sizeof(float) + 20 * 20 * sizeof(float);
 }
 
 bppsa_status bppsa_scan_h20(int T, int B, const float* Jt, const float* seed, float* G, float* g0,
-                            void* workspace, hipStream_t stream);
+                            void* workspace, hipStream_t stream, const float* h = nullptr,
+                            const float* w_hh = nullptr);
 
 bppsa_status bppsa_scan_generic(int T, int B, int H, const float* Jt, const float* seed,
                                 float* G, float* g0, void* workspace, hipStream_t stream);

@@ -185,3 +185,37 @@ def test_scan_h20_fallback_when_dies_stand_aside(bp, mask, monkeypatch):
     assert int(ws[:4].view(torch.int32).item()) == 0          # no bounded wait expired
     assert rel_err(G, G_ref) <= TOL
     assert np.array_equal(G, G_normal)                        # same bits as the die-local path
+
+
+@pytest.mark.parametrize("T,B,want_g0", [(1, 2, False), (1, 2, True), (16, 2, True), (33, 8, False), (130, 5, True),
+                                         (1000, 16, False), (2100, 16, True)])
+def test_rnn_scan_fused_matches_two_call_path_and_oracle(bp, T, B, want_g0):
+    """bppsa_rnn_scan_fused: same bits as build_jacobians + scan, and the oracle's gradients."""
+    import torch
+    H = 20
+    w = workloads.rnn_inputs_norm_preserving(T, B, seed=T + B, gain=1.05) if T >= 1000 else workloads.rnn_inputs(T, B, H, 1, 10, seed=T)
+    h64 = orn.forward(w["x"], w["w_ih"], w["w_hh"], w["b"])
+    h32 = np.asarray(h64, np.float32)              # both sides start from the same fp32 states
+    _, seed = orn.head(h32[-1].astype(np.float64), w["w_out"], w["b_out"], w["labels"])
+    G_ref, g0_ref = orn.backward_chain(h32.astype(np.float64), w["w_hh"], seed)
+    dh, dw, dseed = to_gpu(h32), to_gpu(w["w_hh"]), to_gpu(np.asarray(seed, np.float32))
+    g0a = torch.empty((B, H), dtype=torch.float32, device="cuda") if want_g0 else None
+    g0b = torch.empty((B, H), dtype=torch.float32, device="cuda") if want_g0 else None
+    Jt = bp.build_jacobians(bp.RNN_TANH, dh, w_hh=dw)
+    G_two = to_np(bp.scan(Jt, dseed, g0=g0a))
+    G_fused = to_np(bp.rnn_scan_fused(dh, dw, dseed, g0=g0b))
+    torch.cuda.synchronize()
+    assert np.array_equal(G_fused, G_two)
+    assert rel_err(G_fused, G_ref) <= TOL
+    if want_g0:
+        assert np.array_equal(to_np(g0a), to_np(g0b))
+        assert rel_err(to_np(g0b), g0_ref) <= TOL * max(1.0, np.max(np.abs(G_ref)) / max(np.max(np.abs(g0_ref)), 1e-300))
+
+
+def test_rnn_scan_fused_rejects_other_sizes(bp):
+    import torch
+    h = torch.zeros((5, 2, 16), dtype=torch.float32, device="cuda")
+    w = torch.zeros((16, 16), dtype=torch.float32, device="cuda")
+    s = torch.zeros((2, 16), dtype=torch.float32, device="cuda")
+    with pytest.raises(bp.BppsaError):
+        bp.rnn_scan_fused(h, w, s)
