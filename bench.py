@@ -26,10 +26,10 @@ HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E bandwidth
 # calibration copy (FETCH_SIZE reads 375,011.5 KiB for 750,000 KiB fetched: scale 2.000; WRITE_SIZE
 # reads 750,008.4 for 750,000 written: scale 1.000).  Offline figures: the counters cannot be read
 # inside this process.  Keyed by (T, B, H); the summaries are the profiles/*.txt of the same workloads.
-PMC_COPY_SCALE = {"FETCH_SIZE": 750000.0 / 375011.5391, "WRITE_SIZE": 750000.0 / 750008.3906}
+PMC_COPY_SCALE = {"FETCH_SIZE": 750000.0 / 375011.5703, "WRITE_SIZE": 750000.0 / 750007.4062}
 PMC_SCAN_KIB = {
-    (1000, 16, 20): {"FETCH_SIZE": 13612.8356, "WRITE_SIZE": 2420.0404},
-    (30000, 16, 20): {"FETCH_SIZE": 402720.7596, "WRITE_SIZE": 72385.0481},
+    (1000, 16, 20): {"FETCH_SIZE": 13619.4212, "WRITE_SIZE": 2346.5000},
+    (30000, 16, 20): {"FETCH_SIZE": 402714.2163, "WRITE_SIZE": 70381.9135},
 }
 
 
@@ -165,20 +165,20 @@ def time_scan_only(bp, b, steps, warmup):
     return statistics.mean(a.elapsed_time(z) for a, z in evs)
 
 
-def long_scan(bp, workloads, steps):
+def long_scan(bp, workloads, steps, fused=True):
     """bppsa_scan alone on configs[2] (T=30000): the HBM-bound case of the scan."""
     w2 = workloads.config_inputs(2)
     b2 = prepare(bp, w2)
     bp.build_jacobians(bp.RNN_TANH, b2["h"], w_hh=b2["w_hh"], Jt=b2["Jt"])
     ms = time_scan_only(bp, b2, steps=max(5, min(50, steps)), warmup=3)
-    _, fused_ms = time_fused(bp, b2, max(5, min(50, steps)), 3)
+    fused_ms = time_fused(bp, b2, max(5, min(50, steps)), 3)[1] if fused else None
     nbytes = scan_algorithmic_bytes(w2["T"], w2["B"], w2["H"])
     gbps = nbytes / (ms * 1e-3) / 1e9
     return {"workload": "rnn_tanh_H20_I1_T30000_B16 (configs[2])", "scan_ms": round(ms, 5),
             "algorithmic_bytes": nbytes, "gbps": round(gbps, 2),
             "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 5),
             "traffic": measured_traffic_bytes(w2["T"], w2["B"], w2["H"]),
-            "fused_scan_ms": round(fused_ms, 5)}
+            "fused_scan_ms": None if fused_ms is None else round(fused_ms, 5)}
 
 
 def copy_calibration(bp, steps):
@@ -350,6 +350,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-long", action="store_true", help="skip the T=30000 scan figure")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--no-fused", action="store_true",
+                    help="skip the bppsa_rnn_scan_fused figures (profiling runs: keeps the kernel's launches uniform)")
     ap.add_argument("--long-only", action="store_true",
                     help="time only the T=30000 scan (for profiling); prints its JSON object")
     ap.add_argument("--gru", action="store_true",
@@ -374,7 +376,7 @@ def main():
         sys.exit(1)
 
     if args.long_only:
-        print(json.dumps(long_scan(bp, workloads, args.steps)))
+        print(json.dumps(long_scan(bp, workloads, args.steps, fused=not args.no_fused)))
         return
     if args.gru:
         print(json.dumps(gru_workload(bp, workloads, args.steps)))
@@ -392,7 +394,7 @@ def main():
     wall_ms, parts = time_steps(bp, bufs, args.steps, args.warmup)
 
     cold_ms = time_steps_cold(bp, bufs, max(5, min(30, args.steps)))
-    fused_wall_ms, fused_scan_ms = time_fused(bp, bufs, args.steps, args.warmup)
+    fused_wall_ms, fused_scan_ms = (None, None) if args.no_fused else time_fused(bp, bufs, args.steps, args.warmup)
     scan_bytes = scan_algorithmic_bytes(T, B, H)
     scan_gbps = scan_bytes / (parts["scan_ms"] * 1e-3) / 1e9
     out = {
@@ -413,8 +415,8 @@ def main():
         "breakdown_ms": {k: round(v, 5) for k, v in parts.items()},
         "cold_cache_step_ms": round(cold_ms, 5),
         "fused_path": {"what": "bppsa_rnn_scan_fused + bppsa_param_grads (Jacobians generated inside the scan, "
-                               "never stored); not the metric above", "step_ms": round(fused_wall_ms, 5),
-                       "scan_ms": round(fused_scan_ms, 5)},
+                               "never stored); not the metric above", "step_ms": None if fused_wall_ms is None else round(fused_wall_ms, 5),
+                       "scan_ms": None if fused_scan_ms is None else round(fused_scan_ms, 5)},
         "scan_gbps": round(scan_gbps, 2),
         "roofline": {"kernel": "bppsa_scan", "bound": "hbm", "achieved": round(scan_gbps, 2),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(scan_gbps / HBM_PEAK_GBPS, 5),
@@ -424,7 +426,7 @@ def main():
     if not args.no_long:
         del bufs
         torch.cuda.empty_cache()
-        out["long_scan"] = long_scan(bp, workloads, args.steps)
+        out["long_scan"] = long_scan(bp, workloads, args.steps, fused=not args.no_fused)
         # the box's own streaming rate (768 MB read + 768 MB written), for context beside the 8 TB/s peak
         cal = copy_calibration(bp, 10)
         torch.cuda.empty_cache()
