@@ -4,7 +4,7 @@
 One "step" = bppsa_build_jacobians + bppsa_scan + bppsa_param_grads on the
 vanilla tanh RNN workload H=20, I=1, T=1000, B=16 (the paper's headline point,
 Section 5.1), with hidden states, inputs and weights already resident in HBM.
-Prints ONE JSON line; see the design doc for how each field is derived.
+Prints ONE JSON line.
 """
 from __future__ import annotations
 
