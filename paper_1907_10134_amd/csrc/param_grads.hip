@@ -173,7 +173,7 @@ rnn_param_finish_kernel(int nblocks, int H, int I, const float* __restrict__ par
 }
 
 int rnn_blocks(long long rows) {
-  long long nb = (rows + kTileRows - 1) / kTileRows;
+  long long nb = (rows + 2 * kTileRows - 1) / (2 * kTileRows);
   if (nb > kMaxBlocks) nb = kMaxBlocks;
   return (int)nb;
 }
