@@ -82,6 +82,17 @@ def test_bad_arguments_are_rejected_before_any_launch(lib):
     assert lib.bppsa_csr_conv3x3_indptr(4096, 4096, 64, 64, null, one, null) == EOVERFLOW
     lib.bppsa_head_seed.argtypes = [ctypes.c_int] * 3 + [ctypes.c_void_p] * 7
     assert lib.bppsa_head_seed(1, 4, 65, one, one, one, one, one, null, null) == ESHAPE
+    lib.bppsa_rnn_scan_fused.argtypes = [ctypes.c_int] * 3 + [ctypes.c_void_p] * 6 + [ctypes.c_size_t, ctypes.c_void_p]
+    assert lib.bppsa_rnn_scan_fused(0, 1, 20, one, one, one, one, null, one, 1 << 30, null) == EINVAL
+    assert lib.bppsa_rnn_scan_fused(8, 2, 20, null, one, one, one, null, one, 1 << 30, null) == EINVAL
+    assert lib.bppsa_rnn_scan_fused(8, 2, 16, one, one, one, one, null, one, 1 << 30, null) == EUNSUPPORTED
+    assert lib.bppsa_rnn_scan_fused(1000, 16, 20, one, one, one, one, null, one, 512, null) == EWORKSPACE
+    assert lib.bppsa_rnn_scan_fused(1000, 16, 20, one, one, one, one, null, ctypes.c_void_p(260), 1 << 30, null) == EINVAL
+    lib.bppsa_calibration_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]
+    assert lib.bppsa_calibration_copy(null, one, 16, null) == EINVAL
+    assert lib.bppsa_calibration_copy(one, one, 0, null) == EINVAL
+    assert lib.bppsa_calibration_copy(one, one, 6, null) == ESHAPE
+    assert lib.bppsa_calibration_copy(ctypes.c_void_p(260), one, 16, null) == ESHAPE
 
 
 def test_bench_refuses_more_than_one_gpu():
