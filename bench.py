@@ -413,7 +413,7 @@ def main():
         "config": {"workload": "rnn_tanh_H20_I1_T1000_B16 (configs[1])", "T": T, "B": B, "H": H,
                    "parallelism": "single-gpu"},
         "paper_context": "context, not the target: the paper reports a 16x backward-pass speedup for this workload "
-                         "on an RTX 2070 (Section 5.1) and up to 108x over its sweeps on an RTX 2080 Ti (Section 5.3); "
+                         "on an RTX 2070 and up to 108x over its sweeps on an RTX 2080 Ti (Section 5.1); "
                          "its Table 4 epoch times imply about 1.7 ms of BPPSA backward work per iteration at T=1000 "
                          "and 7.7 ms at T=30000 (figures that also contain the head's backward and the optimizer step)",
         "breakdown_ms": {k: round(v, 5) for k, v in parts.items()},
