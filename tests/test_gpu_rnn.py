@@ -219,3 +219,49 @@ def test_rnn_scan_fused_rejects_other_sizes(bp):
     s = torch.zeros((2, 16), dtype=torch.float32, device="cuda")
     with pytest.raises(bp.BppsaError):
         bp.rnn_scan_fused(h, w, s)
+
+
+def test_three_calls_can_be_captured_in_a_hip_graph(bp):
+    """The hot-path calls enqueue kernels only (no allocation, no memset node), so a caller may
+    capture them; every replay, with eager work in between, must reproduce the eager result."""
+    import torch
+    w = workloads.rnn_inputs(200, 16, 20, 1, 10, seed=5)
+    T, B, H, I = 200, 16, 20, 1
+    d = {k: to_gpu(w[k]) for k in ("x", "w_ih", "w_hh", "b", "w_out", "b_out")}
+    h = torch.zeros((T + 1, B, H), dtype=torch.float32, device="cuda")
+    bp.forward(bp.RNN_TANH, d["x"], d["w_ih"], d["w_hh"], d["b"], None, h)
+    seed, _ = bp.head_seed(h[-1].contiguous(), d["w_out"], d["b_out"], to_gpu(w["labels"]))
+    Jt = torch.empty((T, B, H, H), dtype=torch.float32, device="cuda")
+    G = torch.empty((T, B, H), dtype=torch.float32, device="cuda")
+    ws = torch.empty(bp.scan_workspace_bytes(T, B, H), dtype=torch.uint8, device="cuda")
+    pws = torch.empty(max(bp.param_grads_workspace_bytes(bp.RNN_TANH, T, B, H, I), 256), dtype=torch.uint8, device="cuda")
+    out = (torch.empty((H, I), device="cuda"), torch.empty((H, H), device="cuda"),
+           torch.empty((H,), device="cuda"), torch.empty((H,), device="cuda"))
+
+    def step():
+        bp.build_jacobians(bp.RNN_TANH, h, w_hh=d["w_hh"], Jt=Jt)
+        bp.scan(Jt, seed, G=G, g0=None, workspace=ws)
+        bp.param_grads(bp.RNN_TANH, h, d["x"], G, out=out, workspace=pws)
+
+    step()
+    torch.cuda.synchronize()
+    ref = [t.clone() for t in out] + [G.clone()]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for _ in range(4):
+        G.zero_()
+        for t in out:
+            t.zero_()
+        ws.fill_(0xAB)                         # the workspace may hold anything between calls
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert all(torch.equal(a, r) for a, r in zip(list(out) + [G], ref))
+        step()                                  # eager work between the replays
+        torch.cuda.synchronize()
