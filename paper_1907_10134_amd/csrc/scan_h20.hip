@@ -714,7 +714,12 @@ bppsa_status bppsa_scan_h20(int T, int B, const float* Jt, const float* seed, fl
     scan_h20_kernel<true><<<grid, kThreads, 0, stream>>>(T, B, n, nseg, kMaxQueues, skip_dies, Jt, seed, G, g0, hdr,
                                                          status, agg, incl, Jt ? nullptr : h, wt BPPSA_TRACE_ARG);
   } else {
-    scan_h20_kernel<false><<<grid, kThreads, 0, stream>>>(T, B, n, nseg, 1, 0, Jt, seed, G, g0, hdr, status,
+    // device-scope form: as many queues as the largest divisor of B up to 8, so that the ticket
+    // counters are spread and every queue carries the same number of samples
+    int nq = 1;
+    for (int d = 2; d <= kMaxQueues; ++d)
+      if (B % d == 0) nq = d;
+    scan_h20_kernel<false><<<grid, kThreads, 0, stream>>>(T, B, n, nseg, nq, 0, Jt, seed, G, g0, hdr, status,
                                                           agg, incl, Jt ? nullptr : h, wt BPPSA_TRACE_ARG);
   }
   BPPSA_CHECK_LAUNCH();

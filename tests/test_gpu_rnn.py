@@ -53,7 +53,8 @@ SCAN_SHAPES = [(1, 2, 20), (2, 2, 20), (3, 1, 5), (63, 2, 20), (64, 2, 20), (65,
                (127, 2, 16), (128, 2, 20), (129, 2, 20), (130, 16, 20), (200, 2, 32), (257, 3, 1),
                (300, 2, 2), (70, 2, 33), (131, 1, 64), (67, 2, 128), (1000, 16, 20), (4300, 2, 20),
                (200, 2, 128), (257, 3, 128), (130, 1, 128), (193, 2, 128),
-               (1, 8, 20), (2, 16, 20), (33, 8, 20), (34, 24, 20), (97, 40, 20), (700, 32, 20)]
+               (1, 8, 20), (2, 16, 20), (33, 8, 20), (34, 24, 20), (97, 40, 20), (700, 32, 20),
+               (150, 12, 20), (100, 6, 20), (90, 9, 20), (1100, 10, 20)]
 
 
 @pytest.mark.parametrize("T,B,H", SCAN_SHAPES)
