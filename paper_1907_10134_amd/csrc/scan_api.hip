@@ -49,8 +49,5 @@ extern "C" bppsa_status bppsa_rnn_scan_fused(int T, int B, int H, const float* h
   const size_t need = scan_ws_bytes(T, B, H);
   if (!workspace || workspace_bytes < need) return BPPSA_EWORKSPACE;
   if ((uintptr_t)workspace & 255) return BPPSA_EINVAL;
-  if (T == 1 && !g0) {                           // G[0] = seed, nothing to multiply
-    return bppsa_scan_generic(T, B, H, nullptr, seed, G, g0, workspace, (hipStream_t)stream);
-  }
   return bppsa_scan_h20(T, B, nullptr, seed, G, g0, workspace, (hipStream_t)stream, h, w_hh);
 }

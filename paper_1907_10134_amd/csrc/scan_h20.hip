@@ -685,6 +685,8 @@ bppsa_status bppsa_scan_h20(int T, int B, const float* Jt, const float* seed, fl
                             void* workspace, hipStream_t stream, const float* h, const float* w_hh) {
   const int n = g0 ? T : T - 1;                 // chain elements Jt[T-1] .. Jt[T-n]
   if (n <= 0) {                                 // T == 1 without g0: only G[0] = seed (no Jacobian is read)
+    clear_kernel<<<1, 64, 0, stream>>>(static_cast<int*>(workspace), 1, nullptr, nullptr);   // the error word
+    BPPSA_CHECK_LAUNCH();
     return bppsa_scan_generic(T, B, H, Jt, seed, G, g0, workspace, stream);
   }
   const int nseg = bppsa_ceil_div(n, S);

@@ -266,3 +266,15 @@ def test_three_calls_can_be_captured_in_a_hip_graph(bp):
         assert all(torch.equal(a, r) for a, r in zip(list(out) + [G], ref))
         step()                                  # eager work between the replays
         torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("T,B", [(1, 8), (1, 3), (40, 16), (70, 5)])
+def test_scan_h20_error_word_is_zero_after_a_normal_call(bp, T, B):
+    """The workspace may hold anything on entry; its first word reads 0 after a normal call."""
+    import torch
+    jt, seed = workloads.random_jacobian_chain(T, B, 20, seed=T + B)
+    ws = torch.full((bp.scan_workspace_bytes(T, B, 20),), 0xC3, dtype=torch.uint8, device="cuda")
+    G = bp.scan(to_gpu(jt), to_gpu(seed), workspace=ws)
+    torch.cuda.synchronize()
+    assert int(ws[:4].view(torch.int32).item()) == 0
+    assert np.array_equal(to_np(G[T - 1]), seed)
