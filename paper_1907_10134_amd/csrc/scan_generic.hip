@@ -13,6 +13,8 @@
 //   apply  : every other segment walks its steps with matrix-vector products
 //            from its incoming vector (the down-sweep side).
 // Any bracketing gives the same gradients up to rounding (Section 3.5).
+#include <mutex>
+
 #include "bppsa_internal.h"
 #include "scan_plan.h"
 
@@ -166,6 +168,96 @@ bppsa_status launch_apply(int T, int B, int H, int t_min, int S, int seg_begin, 
   return BPPSA_OK;
 }
 
+// A second stream and the events that order it against the caller's stream; one set per
+// device, created on first use and kept until the process ends.  `lock` is held while a call
+// enqueues work that uses them, so that the records and waits of two host threads do not
+// interleave.
+constexpr int kMaxSlabs = 32;
+struct SideStream {
+  hipStream_t stream;
+  hipEvent_t fork, join, slab[kMaxSlabs];
+  std::mutex lock;
+};
+SideStream* side_stream() {
+  constexpr int kMaxDevices = 64;
+  static SideStream table[kMaxDevices];
+  static bool made[kMaxDevices];
+  static std::mutex table_lock;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> hold(table_lock);
+  if (!made[dev]) {
+    SideStream& st = table[dev];
+    if (hipStreamCreateWithFlags(&st.stream, hipStreamNonBlocking) != hipSuccess) return nullptr;
+    if (hipEventCreateWithFlags(&st.fork, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&st.join, hipEventDisableTiming) != hipSuccess)
+      return nullptr;
+    for (int i = 0; i < kMaxSlabs; ++i)
+      if (hipEventCreateWithFlags(&st.slab[i], hipEventDisableTiming) != hipSuccess) return nullptr;
+    made[dev] = true;
+  }
+  return &table[dev];
+}
+
+int compute_units() {
+  static int cached = 0;
+  if (!cached) {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+      cus = 256;
+    cached = cus;
+  }
+  return cached;
+}
+
+// H = 128, long chains: the matrix-matrix totals (bound by the matrix cores, little memory
+// traffic) and the matrix-vector passes (bound by HBM, little arithmetic) run side by side.
+// The interior segments are cut into slabs, nearest the seed first, each slab filling the
+// device once.  The caller's stream forms the totals slab by slab; a second stream follows
+// one slab behind: chain of the slab's totals from the vector handed on by the previous slab,
+// then the slab's own matrix-vector pass.  A workgroup of either kind fits beside the other
+// on a compute unit (188 + 148 registers per lane, 135 KB + 1 KB of LDS).
+bppsa_status scan_h128_pipelined(int T, int B, int t_min, int S, int nseg, const float* Jt, const float* seed,
+                                 float* G, float* g0, float* tot, float* vin, hipStream_t s, SideStream* side,
+                                 int slab) {
+  constexpr int H = 128;
+  const size_t row = (size_t)B * H;
+  std::lock_guard<std::mutex> hold(side->lock);
+  hipStream_t s2 = side->stream;
+  BPPSA_HIP_TRY(hipEventRecord(side->fork, s));
+  BPPSA_HIP_TRY(hipStreamWaitEvent(s2, side->fork, 0));
+  // seed-side segment: matrix-vector only; its last vector enters segment nseg-2
+  bppsa_status st = launch_apply(T, B, H, t_min, S, nseg - 1, 1, Jt, seed, 1, G, g0,
+                                 vin + (size_t)(nseg - 2) * row, s2);
+  if (st != BPPSA_OK) return st;
+  int j = 0;
+  for (int hi = nseg - 2; hi >= 0; ++j) {
+    int lo = hi - slab + 1;
+    if (lo <= 1) lo = 0;                        // segment 0 has no total: it rides with the last slab
+    const int rlo = lo < 1 ? 1 : lo;            // totals exist for segments 1 .. nseg-2
+    if (hi >= rlo) {
+      st = launch_reduce(T, B, H, t_min, S, rlo, hi - rlo + 1, Jt, tot, s);
+      if (st != BPPSA_OK) return st;
+    }
+    BPPSA_HIP_TRY(hipEventRecord(side->slab[j], s));
+    BPPSA_HIP_TRY(hipStreamWaitEvent(s2, side->slab[j], 0));
+    if (hi >= rlo) {
+      // vin[seg-1] = tot[seg] vin[seg] for seg = hi .. rlo: the totals as a chain of hi-rlo+1
+      // steps, entered by vin[hi]; also gives the next slab its entering vector
+      st = launch_apply(hi + 1, B, H, rlo, hi - rlo + 1, 0, 1, tot, vin + (size_t)hi * row, 1, vin, nullptr,
+                        nullptr, s2);
+      if (st != BPPSA_OK) return st;
+    }
+    st = launch_apply(T, B, H, t_min, S, lo, hi - lo + 1, Jt, vin, 0, G, g0, nullptr, s2);
+    if (st != BPPSA_OK) return st;
+    hi = lo - 1;
+  }
+  BPPSA_HIP_TRY(hipEventRecord(side->join, s2));
+  BPPSA_HIP_TRY(hipStreamWaitEvent(s, side->join, 0));
+  return BPPSA_OK;
+}
+
 // One level of the recursion; `ws` is the unused tail of the workspace.
 bppsa_status scan_level(int T, int B, int H, const float* Jt, const float* seed,
                         float* G, float* g0, char* ws, hipStream_t s) {
@@ -189,6 +281,13 @@ bppsa_status scan_level(int T, int B, int H, const float* Jt, const float* seed,
   ws += bppsa_align_up((size_t)T2 * row * sizeof(float), 256);
 
   bppsa_status st;
+  if (H == 128) {
+    int slab = compute_units() / B;             // segments whose totals fill the device once
+    if (slab < 1) slab = 1;
+    if (bppsa_ceil_div(nseg - 1, slab) > kMaxSlabs) slab = bppsa_ceil_div(nseg - 1, kMaxSlabs);
+    SideStream* side = (nseg - 2 >= 2 * slab) ? side_stream() : nullptr;
+    if (side) return scan_h128_pipelined(T, B, t_min, S, nseg, Jt, seed, G, g0, tot, vin, s, side, slab);
+  }
   // interior segments 1..nseg-2: matrix-matrix totals (segment 0's total reaches no output)
   st = launch_reduce(T, B, H, t_min, S, 1, nseg - 2, Jt, tot, s);
   if (st != BPPSA_OK) return st;

@@ -155,6 +155,8 @@ apply_h128_kernel(int T, int B, int t_min, int S, int seg_begin, const float* __
                   const float* __restrict__ vin, int vin_is_seed, float* __restrict__ G,
                   float* __restrict__ g0, float* __restrict__ v_out) {
   __shared__ __attribute__((aligned(16))) float vs[2][H];
+  // this kernel may share a compute unit with the matrix-core kernel of the pipelined form
+  __builtin_amdgcn_s_setprio(3);
   const int tid = threadIdx.x;
   const int c = tid & 31, r = tid >> 5;
   const int seg = seg_begin + blockIdx.x;

@@ -115,3 +115,55 @@ def test_gru_config3_full_size(bp):
     for t in [0, 1, 4095] + list(rng.integers(2, 4095, size=5)):
         ref = ogru.step_jacobian_T(h[t], w["x"][t], *args)
         assert rel_err(to_np(Jt[int(t)]), ref) <= 2e-6
+
+
+def test_h128_long_scan_in_a_hip_graph_and_link_by_link(bp):
+    """A chain long enough for the form of the H=128 scan that runs its matrix-matrix and its
+    matrix-vector kernels side by side on two streams (2304 steps, B=16: 2.4 GB of Jacobians).
+    Properties that hold at any size: the top gradient is the seed, every link satisfies
+    g[t] = Jt[t] g[t+1] (checked on the device's own g[t+1] for sampled t), repeated calls and
+    replays of a captured graph return the same bits whatever the workspace held."""
+    import torch
+    T, B, H = 2304, 16, 128
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(1234)
+    Jt = torch.empty((T, B, H, H), dtype=torch.float32, device="cuda")
+    for t0 in range(0, T, 256):                  # near-isometries: identity plus a small random part
+        blk = Jt[t0:t0 + 256]
+        blk.normal_(0.0, 0.03 / np.sqrt(H), generator=gen)
+        blk.diagonal(dim1=-2, dim2=-1).add_(1.0)
+    seed = torch.randn((B, H), dtype=torch.float32, device="cuda", generator=gen)
+    ws = torch.empty(bp.scan_workspace_bytes(T, B, H), dtype=torch.uint8, device="cuda")
+    G = torch.empty((T, B, H), dtype=torch.float32, device="cuda")
+    g0 = torch.empty((B, H), dtype=torch.float32, device="cuda")
+    bp.scan(Jt, seed, G=G, g0=g0, workspace=ws)
+    torch.cuda.synchronize()
+    ref, ref0 = G.clone(), g0.clone()
+    assert torch.equal(G[T - 1], seed)
+    scale = float(G.abs().max())
+    rng = np.random.default_rng(7)
+    for t in [1, 63, 64, 65, 1023, 1024, T - 1] + [int(v) for v in rng.integers(1, T, size=20)]:
+        want = torch.bmm(Jt[t].double(), G[t].double().unsqueeze(-1)).squeeze(-1)
+        assert float((G[t - 1].double() - want).abs().max()) <= TOL * scale
+    want0 = torch.bmm(Jt[0].double(), G[0].double().unsqueeze(-1)).squeeze(-1)
+    assert float((g0.double() - want0).abs().max()) <= TOL * scale
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        bp.scan(Jt, seed, G=G, g0=g0, workspace=ws)
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        bp.scan(Jt, seed, G=G, g0=g0, workspace=ws)
+    for _ in range(3):
+        G.zero_()
+        g0.zero_()
+        ws.fill_(0x5A)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(G, ref) and torch.equal(g0, ref0)
+        bp.scan(Jt, seed, G=G, g0=g0, workspace=ws)      # eager work between the replays
+        torch.cuda.synchronize()
+        assert torch.equal(G, ref) and torch.equal(g0, ref0)
