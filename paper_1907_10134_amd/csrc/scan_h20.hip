@@ -370,6 +370,11 @@ __device__ __forceinline__ void drain_queue(int qid, int T, int B, int n, int ns
   float* const vin = sh.vin;
   const int bq = (B - qid + nq - 1) / nq;        // samples of this queue: qid, qid + nq, ...
   const int quota = nseg * bq;
+  // The ticket of the next segment is requested while the current one is in its down-sweep
+  // (below), so that the round trip of the atomic - and of the gradient stores issued before
+  // it, which return on the same counter - is off the path between two segments.
+  if (threadIdx.x == 0) *sh.ticket_s = __hip_atomic_fetch_add(&hdr->ticket[qid][0], 1, __ATOMIC_RELAXED, SCOPE);
+  __syncthreads();
   for (;;) {
     // Re-derive the lane coordinates inside the loop from an opaque copy of the thread id:
     // otherwise every LDS address of the body is hoisted out of the loop and the hoisted
@@ -377,8 +382,6 @@ __device__ __forceinline__ void drain_queue(int qid, int T, int B, int n, int ns
     int tid = threadIdx.x;
     asm volatile("" : "+v"(tid));
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, slot = lane >> 2, q = lane & 3;
-    if (tid == 0) *sh.ticket_s = __hip_atomic_fetch_add(&hdr->ticket[qid][0], 1, __ATOMIC_RELAXED, SCOPE);
-    __syncthreads();
     const int ticket = __builtin_amdgcn_readfirstlane(*sh.ticket_s);
     if (ticket >= quota) break;                  // uniform: the queue is empty
     const int k = ticket / bq;                   // segment, 0 = seed end
@@ -508,6 +511,9 @@ __device__ __forceinline__ void drain_queue(int qid, int T, int B, int n, int ns
     }
     __syncthreads();
     BPPSA_STAMP(4);
+    // next ticket: no wait is left in this segment, so holding it delays nobody
+    int next_ticket = 0;
+    if (tid == 0) next_ticket = __hip_atomic_fetch_add(&hdr->ticket[qid][0], 1, __ATOMIC_RELAXED, SCOPE);
 
     // ---- down-sweep: T <- a[l]; a[l] <- a[r]; a[r] <- T a[r] ----------------------------
     if (tid < H) vec[(S - 1) * H + tid] = vin[tid];
@@ -588,6 +594,7 @@ __device__ __forceinline__ void drain_queue(int qid, int T, int B, int n, int ns
     // gradients of a long sequence are streamed past the caches; a short one is left in cache
     // for the parameter-gradient pass that follows
     const bool stream_out = (size_t)T * B * H * sizeof(float) > ((size_t)64 << 20);
+    if (tid == 0) *sh.ticket_s = next_ticket;     // every thread read the current one long ago
     for (int e = tid; e < m * H; e += kThreads) {
       const int p = e / H, row = e - p * H;
       float* dst = G + ((size_t)(T - 1 - c0 - p) * B + b) * H + row;
