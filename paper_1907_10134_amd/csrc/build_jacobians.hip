@@ -73,7 +73,11 @@ rnn_jacobians_h20_kernel(int tiles, int B, const float* __restrict__ h, const fl
   const int step = gridDim.x * kH20TilesPerPass;
   for (int m = blockIdx.x * kH20TilesPerPass + slot; m < tiles; m += step) {
     const bj_v4f hv = *reinterpret_cast<const bj_v4f*>(h + (size_t)(m + B) * H + j4);   // h[t+1][b][j4..]
-    const bj_v4f o = w * (1.0f - hv * hv);
+    // 1 - h^2 as one fused multiply-add, spelled out: the fused scan forms the same tile and
+    // must get the same bits whatever the compiler would contract
+    bj_v4f o;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) o[u] = w[u] * __builtin_fmaf(-hv[u], hv[u], 1.0f);
     bj_v4f* dst = reinterpret_cast<bj_v4f*>(Jt + (size_t)m * H * H + p * 4);
     if (STREAM) __builtin_nontemporal_store(o, dst);   // far larger than the caches: do not allocate
     else *dst = o;                                     // small enough to be read back from cache

@@ -414,7 +414,8 @@ __device__ __forceinline__ void drain_queue(int qid, int T, int B, int n, int ns
             const int i = off / 5, j4 = (off - i * 5) * 4;
             const v4f wv = *reinterpret_cast<const v4f*>(wt + i * H + j4);
             const v4f hv = *reinterpret_cast<const v4f*>(hsrc + ((size_t)(T - c0 - p) * B + b) * H + j4);
-            tmp[r] = wv * (1.0f - hv * hv);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) tmp[r][u] = wv[u] * __builtin_fmaf(-hv[u], hv[u], 1.0f);   // as the builder
           } else {
             const float* src = Jt + ((size_t)(T - 1 - c0 - p) * B + b) * HH;
             tmp[r] = reinterpret_cast<const v4f*>(src)[off];
