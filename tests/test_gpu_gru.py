@@ -117,19 +117,20 @@ def test_gru_config3_full_size(bp):
         assert rel_err(to_np(Jt[int(t)]), ref) <= 2e-6
 
 
-def test_h128_long_scan_in_a_hip_graph_and_link_by_link(bp):
-    """A chain long enough for the form of the H=128 scan that runs its matrix-matrix and its
-    matrix-vector kernels side by side on two streams (2304 steps, B=16: 2.4 GB of Jacobians).
-    Properties that hold at any size: the top gradient is the seed, every link satisfies
-    g[t] = Jt[t] g[t+1] (checked on the device's own g[t+1] for sampled t), repeated calls and
-    replays of a captured graph return the same bits whatever the workspace held."""
+@pytest.mark.parametrize("T,B", [(2304, 16), (700, 64), (11000, 3), (260, 256)])
+def test_h128_long_scan_in_a_hip_graph_and_link_by_link(bp, T, B):
+    """Chains long enough for the form of the H=128 scan that runs its matrix-matrix and its
+    matrix-vector kernels side by side on two streams (2 to 4 GB of Jacobians; slabs of 16, 4, 85
+    and 1 segments).  Properties that hold at any size: the top gradient is the seed, every link
+    satisfies g[t] = Jt[t] g[t+1] (checked on the device's own g[t+1] for sampled t), repeated
+    calls and replays of a captured graph return the same bits whatever the workspace held."""
     import torch
-    T, B, H = 2304, 16, 128
+    H = 128
     gen = torch.Generator(device="cuda")
     gen.manual_seed(1234)
     Jt = torch.empty((T, B, H, H), dtype=torch.float32, device="cuda")
-    for t0 in range(0, T, 256):                  # near-isometries: identity plus a small random part
-        blk = Jt[t0:t0 + 256]
+    for t0 in range(0, T, 64):                   # near-isometries: identity plus a small random part
+        blk = Jt[t0:t0 + 64]
         blk.normal_(0.0, 0.03 / np.sqrt(H), generator=gen)
         blk.diagonal(dim1=-2, dim2=-1).add_(1.0)
     seed = torch.randn((B, H), dtype=torch.float32, device="cuda", generator=gen)
@@ -142,7 +143,7 @@ def test_h128_long_scan_in_a_hip_graph_and_link_by_link(bp):
     assert torch.equal(G[T - 1], seed)
     scale = float(G.abs().max())
     rng = np.random.default_rng(7)
-    for t in [1, 63, 64, 65, 1023, 1024, T - 1] + [int(v) for v in rng.integers(1, T, size=20)]:
+    for t in [1, 63, 64, 65, 127, 128, 129, T - 1] + [int(v) for v in rng.integers(1, T, size=40)]:
         want = torch.bmm(Jt[t].double(), G[t].double().unsqueeze(-1)).squeeze(-1)
         assert float((G[t - 1].double() - want).abs().max()) <= TOL * scale
     want0 = torch.bmm(Jt[0].double(), G[0].double().unsqueeze(-1)).squeeze(-1)
