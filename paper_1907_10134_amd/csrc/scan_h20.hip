@@ -31,9 +31,14 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 
 constexpr int H = 20;
 constexpr int HH = 400;
-constexpr int TS = 404;                 // LDS tile stride in floats: 400 plus one 16-byte pad, so that
-                                        // tiles two apart do not start on the same LDS bank
+constexpr int PS = 2 * HH + 4;           // LDS stride of a pair of tiles in floats: two tiles back to back
+                                        // plus one 16-byte pad.  Level 0 reads the same element of 16
+                                        // even (or 16 odd) tiles at once; with this stride the tiles of
+                                        // eight consecutive pairs start four banks apart, so those reads
+                                        // spread over all 32 banks instead of hitting four of them
 constexpr int S = BPPSA_H20_SEGMENT;
+// offset of tile p of a segment in LDS
+__device__ __forceinline__ constexpr int toff(int p) { return (p >> 1) * PS + (p & 1) * HH; }
 constexpr int kThreads = 256;
 constexpr int kAggStride = BPPSA_H20_AGG_STRIDE;   // floats per published total (1664 B = 13 lines)
 constexpr int kIncStride = BPPSA_H20_INC_STRIDE;   // floats per published vector (128 B)
@@ -430,7 +435,7 @@ __device__ __forceinline__ void drain_queue(int qid, int T, int B, int n, int ns
       for (int r = 0; r < (kChunks + kThreads - 1) / kThreads; ++r) {
         const int e = tid + r * kThreads;
         const int p = e / (HH / 4), off = e - p * (HH / 4);
-        if (e < kChunks) reinterpret_cast<v4f*>(mat + p * TS)[off] = tmp[r];
+        if (e < kChunks) reinterpret_cast<v4f*>(mat + toff(p))[off] = tmp[r];
       }
     }
     __syncthreads();
@@ -439,8 +444,8 @@ __device__ __forceinline__ void drain_queue(int qid, int T, int B, int n, int ns
     // ---- up-sweep level 0: a[2s+1] <- a[2s+1] a[2s] -------------------------------------
     {
       v4f acc[9];
-      float* A = mat + (2 * slot + 1) * TS;
-      const float* Bm = mat + (2 * slot) * TS;
+      float* A = mat + toff(2 * slot + 1);
+      const float* Bm = mat + toff(2 * slot);
       switch (role) {
         case 0: level0_compute<0, 3, 0, 3>(A, Bm, q, acc); break;
         case 1: level0_compute<0, 3, 3, 2>(A, Bm, q, acc); break;
@@ -461,19 +466,19 @@ __device__ __forceinline__ void drain_queue(int qid, int T, int B, int n, int ns
     // Levels 1 and 2 of the eight tiles 8w .. 8w+7 belong to the wave of role w alone: the LDS operations
     // of one wave complete in order, so no workgroup barrier is needed between the two.
     {
-      float* sub = mat + 8 * role * TS;
-      wave_product(sub + 3 * TS, sub + 1 * TS, slot, q);
-      wave_product(sub + 7 * TS, sub + 5 * TS, slot, q);
-      wave_product(sub + 7 * TS, sub + 3 * TS, slot, q);
+      float* sub = mat + toff(8 * role);
+      wave_product(sub + toff(3), sub + toff(1), slot, q);
+      wave_product(sub + toff(7), sub + toff(5), slot, q);
+      wave_product(sub + toff(7), sub + toff(3), slot, q);
     }
     __syncthreads();
     BPPSA_STAMP(12);
-    if (role >= 2) wave_product(mat + (16 * (role - 2) + 15) * TS, mat + (16 * (role - 2) + 7) * TS, slot, q);
+    if (role >= 2) wave_product(mat + toff(16 * (role - 2) + 15), mat + toff(16 * (role - 2) + 7), slot, q);
     __syncthreads();
-    if (role == 1) wave_product(mat + 31 * TS, mat + 15 * TS, slot, q);
+    if (role == 1) wave_product(mat + toff(31), mat + toff(15), slot, q);
     __syncthreads();
     BPPSA_STAMP(2);
-    float* total = mat + (S - 1) * TS;
+    float* total = mat + toff(S - 1);
 
     // ---- publish the segment total (interior segments only) -----------------------------
     if (k > 0 && k < nseg - 1) {
@@ -517,14 +522,38 @@ __device__ __forceinline__ void drain_queue(int qid, int T, int B, int n, int ns
     if (tid == 0) next_ticket = __hip_atomic_fetch_add(&hdr->ticket[qid][0], 1, __ATOMIC_RELAXED, SCOPE);
 
     // ---- down-sweep: T <- a[l]; a[l] <- a[r]; a[r] <- T a[r] ----------------------------
-    if (tid < H) vec[(S - 1) * H + tid] = vin[tid];
-    __syncthreads();
-    // Levels 4, 3 and 2 (1, 2 and 4 pairs) are run by one wave alone, again without workgroup
-    // barriers: every lane's reads of a level are issued before any lane's writes.
-    if (role == 2) {
+    // Matrix-vector products only.  The wave of role w owns the eight elements 8w .. 8w+7 from
+    // here to the store, so no workgroup barrier is needed: it first forms the vector that
+    // levels 4 and 3 leave at the top of its sub-tree (up to two products, repeated by every
+    // wave that needs them) and then runs levels 2, 1 and 0 of that sub-tree.  LDS operations
+    // of one wave complete in order, and every lane's reads of a level are issued before any
+    // lane's writes.
+    {
+      float* const wvec = vec + 8 * role * H;    // vectors entering elements 8w .. 8w+7
+      auto wave_sync = [] {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+      };
+      // level 4 gives element 16 the vector a[15] vin; level 3 gives element 8 a[7] vin and
+      // element 24 a[23] (a[15] vin)
+      if (lane < H) {
+        float u = vin[lane];
+        if (role == 1) u = row_dot(mat + toff(7), lane, vin);
+        if (role >= 2) u = row_dot(mat + toff(15), lane, vin);
+        wvec[7 * H + lane] = u;
+      }
+      wave_sync();
+      if (role == 3) {
+        float u = 0.f;
+        if (lane < H) u = row_dot(mat + toff(23), lane, wvec + 7 * H);
+        wave_sync();
+        if (lane < H) wvec[7 * H + lane] = u;
+        wave_sync();
+      }
 #pragma unroll
-      for (int d = 4; d >= 2; --d) {
-        const int npairs = S >> (d + 1);
+      for (int d = 2; d >= 0; --d) {
+        const int npairs = 8 >> (d + 1);
         float res[2], keep[2];
 #pragma unroll
         for (int r = 0; r < 2; ++r) {
@@ -535,12 +564,11 @@ __device__ __forceinline__ void drain_queue(int qid, int T, int B, int n, int ns
             const int pr = e / H, row = e - pr * H;
             const int i = pr << (d + 1);
             const int l = i + (1 << d) - 1, rr = i + (2 << d) - 1;
-            res[r] = row_dot(mat + l * TS, row, vec + rr * H);
-            keep[r] = vec[rr * H + row];
+            res[r] = row_dot(mat + toff(8 * role + l), row, wvec + rr * H);
+            keep[r] = wvec[rr * H + row];
           }
         }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-        __builtin_amdgcn_wave_barrier();
+        wave_sync();
 #pragma unroll
         for (int r = 0; r < 2; ++r) {
           const int e = lane + 64 * r;
@@ -548,59 +576,29 @@ __device__ __forceinline__ void drain_queue(int qid, int T, int B, int n, int ns
             const int pr = e / H, row = e - pr * H;
             const int i = pr << (d + 1);
             const int l = i + (1 << d) - 1, rr = i + (2 << d) - 1;
-            vec[l * H + row] = keep[r];
-            vec[rr * H + row] = res[r];
+            wvec[l * H + row] = keep[r];
+            wvec[rr * H + row] = res[r];
           }
         }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-        __builtin_amdgcn_wave_barrier();
+        wave_sync();
       }
-    }
-    __syncthreads();
-#pragma unroll
-    for (int d = 1; d >= 0; --d) {
-      const int npairs = S >> (d + 1);
-      float res[2];
-      float keep[2];
-#pragma unroll
-      for (int r = 0; r < 2; ++r) {
-        const int e = tid + r * kThreads;
-        res[r] = 0.f;
-        keep[r] = 0.f;
-        if (e < npairs * H) {
-          const int pr = e / H, row = e - pr * H;
-          const int i = pr << (d + 1);
-          const int l = i + (1 << d) - 1, rr = i + (2 << d) - 1;
-          res[r] = row_dot(mat + l * TS, row, vec + rr * H);
-          keep[r] = vec[rr * H + row];
-        }
-      }
-      __syncthreads();
-#pragma unroll
-      for (int r = 0; r < 2; ++r) {
-        const int e = tid + r * kThreads;
-        if (e < npairs * H) {
-          const int pr = e / H, row = e - pr * H;
-          const int i = pr << (d + 1);
-          const int l = i + (1 << d) - 1, rr = i + (2 << d) - 1;
-          vec[l * H + row] = keep[r];
-          vec[rr * H + row] = res[r];
-        }
-      }
-      __syncthreads();
-    }
 
-    BPPSA_STAMP(5);
-    // ---- store: the vector entering element p is g[T-c0-p] = G[T-1-c0-p] ------------------
-    // gradients of a long sequence are streamed past the caches; a short one is left in cache
-    // for the parameter-gradient pass that follows
-    const bool stream_out = (size_t)T * B * H * sizeof(float) > ((size_t)64 << 20);
-    if (tid == 0) *sh.ticket_s = next_ticket;     // every thread read the current one long ago
-    for (int e = tid; e < m * H; e += kThreads) {
-      const int p = e / H, row = e - p * H;
-      float* dst = G + ((size_t)(T - 1 - c0 - p) * B + b) * H + row;
-      if (stream_out) __builtin_nontemporal_store(vec[e], dst);
-      else *dst = vec[e];
+      BPPSA_STAMP(5);
+      // ---- store: the vector entering element p is g[T-c0-p] = G[T-1-c0-p] ----------------
+      // gradients of a long sequence are streamed past the caches; a short one is left in
+      // cache for the parameter-gradient pass that follows
+      const bool stream_out = (size_t)T * B * H * sizeof(float) > ((size_t)64 << 20);
+      if (tid == 0) *sh.ticket_s = next_ticket;   // every thread read the current one long ago
+#pragma unroll
+      for (int r = 0; r < 3; ++r) {
+        const int e = lane + 64 * r;
+        const int p = 8 * role + e / H, row = e - (e / H) * H;
+        if (e < 8 * H && p < m) {
+          float* dst = G + ((size_t)(T - 1 - c0 - p) * B + b) * H + row;
+          if (stream_out) __builtin_nontemporal_store(wvec[e], dst);
+          else *dst = wvec[e];
+        }
+      }
     }
     BPPSA_STAMP(6);
     __syncthreads();                              // LDS and ticket_s are reused by the next segment
@@ -615,10 +613,10 @@ scan_h20_kernel(int T, int B, int n, int nseg, int nq, int skip_dies, const floa
                 const float* __restrict__ wt BPPSA_TRACE_PARAM) {
   // 32 tiles, then room so that the 32 down-sweep vectors can start on top of the last tile
   // (the segment total, dead once the inclusive vector has been formed)
-  __shared__ __attribute__((aligned(16))) float lds[(S - 1) * TS + S * H];
+  __shared__ __attribute__((aligned(16))) float lds[toff(S - 1) + S * H];
   __shared__ __attribute__((aligned(16))) float vin[H];
   __shared__ int ticket_s;
-  const Shared sh = {lds, lds + (S - 1) * TS, vin, &ticket_s};
+  const Shared sh = {lds, lds + toff(S - 1), vin, &ticket_s};
   if (!LOCAL) {
     const int qid = (int)(blockIdx.x % (unsigned)nq);
     drain_queue<__HIP_MEMORY_SCOPE_AGENT>(qid, T, B, n, nseg, nq, Jt, seed, G, g0, hdr, status, agg, incl, sh,
