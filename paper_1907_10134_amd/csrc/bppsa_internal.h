@@ -36,3 +36,13 @@ static inline bool bppsa_mul_overflows(int64_t a, int64_t b, int64_t c, int64_t 
   if (abc > lim / d) return true;
   return false;
 }
+
+// Compute units of the current device (256 on an MI355X); queried from the runtime on every
+// call, so nothing is remembered across devices.  Falls back to 256 if the query fails.
+static inline int bppsa_compute_units() {
+  int dev = 0, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+    cus = 256;
+  return cus;
+}

@@ -199,18 +199,6 @@ SideStream* side_stream() {
   return &table[dev];
 }
 
-int compute_units() {
-  static int cached = 0;
-  if (!cached) {
-    int dev = 0, cus = 0;
-    if (hipGetDevice(&dev) != hipSuccess ||
-        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
-      cus = 256;
-    cached = cus;
-  }
-  return cached;
-}
-
 // H = 128, long chains: the matrix-matrix totals (bound by the matrix cores, little memory
 // traffic) and the matrix-vector passes (bound by HBM, little arithmetic) run side by side.
 // The interior segments are cut into slabs, nearest the seed first, each slab filling the
@@ -227,35 +215,42 @@ bppsa_status scan_h128_pipelined(int T, int B, int t_min, int S, int nseg, const
   hipStream_t s2 = side->stream;
   BPPSA_HIP_TRY(hipEventRecord(side->fork, s));
   BPPSA_HIP_TRY(hipStreamWaitEvent(s2, side->fork, 0));
-  // seed-side segment: matrix-vector only; its last vector enters segment nseg-2
-  bppsa_status st = launch_apply(T, B, H, t_min, S, nseg - 1, 1, Jt, seed, 1, G, g0,
-                                 vin + (size_t)(nseg - 2) * row, s2);
+  // From here on the second stream carries work of this call, so every way out - an error
+  // included - goes through the join below: the caller's stream waits for whatever was enqueued
+  // on the second stream (and a capturing stream gets its fork joined) before the status returns.
+  bppsa_status st = [&]() -> bppsa_status {
+    // seed-side segment: matrix-vector only; its last vector enters segment nseg-2
+    bppsa_status e = launch_apply(T, B, H, t_min, S, nseg - 1, 1, Jt, seed, 1, G, g0,
+                                  vin + (size_t)(nseg - 2) * row, s2);
+    if (e != BPPSA_OK) return e;
+    int j = 0;
+    for (int hi = nseg - 2; hi >= 0; ++j) {
+      int lo = hi - slab + 1;
+      if (lo <= 1) lo = 0;                        // segment 0 has no total: it rides with the last slab
+      const int rlo = lo < 1 ? 1 : lo;            // totals exist for segments 1 .. nseg-2
+      if (hi >= rlo) {
+        e = launch_reduce(T, B, H, t_min, S, rlo, hi - rlo + 1, Jt, tot, s);
+        if (e != BPPSA_OK) return e;
+      }
+      BPPSA_HIP_TRY(hipEventRecord(side->slab[j], s));
+      BPPSA_HIP_TRY(hipStreamWaitEvent(s2, side->slab[j], 0));
+      if (hi >= rlo) {
+        // vin[seg-1] = tot[seg] vin[seg] for seg = hi .. rlo: the totals as a chain of hi-rlo+1
+        // steps, entered by vin[hi]; also gives the next slab its entering vector
+        e = launch_apply(hi + 1, B, H, rlo, hi - rlo + 1, 0, 1, tot, vin + (size_t)hi * row, 1, vin, nullptr,
+                         nullptr, s2);
+        if (e != BPPSA_OK) return e;
+      }
+      e = launch_apply(T, B, H, t_min, S, lo, hi - lo + 1, Jt, vin, 0, G, g0, nullptr, s2);
+      if (e != BPPSA_OK) return e;
+      hi = lo - 1;
+    }
+    return BPPSA_OK;
+  }();
+  const bool joined = hipEventRecord(side->join, s2) == hipSuccess &&
+                      hipStreamWaitEvent(s, side->join, 0) == hipSuccess;
   if (st != BPPSA_OK) return st;
-  int j = 0;
-  for (int hi = nseg - 2; hi >= 0; ++j) {
-    int lo = hi - slab + 1;
-    if (lo <= 1) lo = 0;                        // segment 0 has no total: it rides with the last slab
-    const int rlo = lo < 1 ? 1 : lo;            // totals exist for segments 1 .. nseg-2
-    if (hi >= rlo) {
-      st = launch_reduce(T, B, H, t_min, S, rlo, hi - rlo + 1, Jt, tot, s);
-      if (st != BPPSA_OK) return st;
-    }
-    BPPSA_HIP_TRY(hipEventRecord(side->slab[j], s));
-    BPPSA_HIP_TRY(hipStreamWaitEvent(s2, side->slab[j], 0));
-    if (hi >= rlo) {
-      // vin[seg-1] = tot[seg] vin[seg] for seg = hi .. rlo: the totals as a chain of hi-rlo+1
-      // steps, entered by vin[hi]; also gives the next slab its entering vector
-      st = launch_apply(hi + 1, B, H, rlo, hi - rlo + 1, 0, 1, tot, vin + (size_t)hi * row, 1, vin, nullptr,
-                        nullptr, s2);
-      if (st != BPPSA_OK) return st;
-    }
-    st = launch_apply(T, B, H, t_min, S, lo, hi - lo + 1, Jt, vin, 0, G, g0, nullptr, s2);
-    if (st != BPPSA_OK) return st;
-    hi = lo - 1;
-  }
-  BPPSA_HIP_TRY(hipEventRecord(side->join, s2));
-  BPPSA_HIP_TRY(hipStreamWaitEvent(s, side->join, 0));
-  return BPPSA_OK;
+  return joined ? BPPSA_OK : BPPSA_EHIP;
 }
 
 // One level of the recursion; `ws` is the unused tail of the workspace.
@@ -282,7 +277,7 @@ bppsa_status scan_level(int T, int B, int H, const float* Jt, const float* seed,
 
   bppsa_status st;
   if (H == 128) {
-    int slab = compute_units() / B;             // segments whose totals fill the device once
+    int slab = bppsa_compute_units() / B;             // segments whose totals fill the device once
     if (slab < 1) slab = 1;
     if (bppsa_ceil_div(nseg - 1, slab) > kMaxSlabs) slab = bppsa_ceil_div(nseg - 1, kMaxSlabs);
     SideStream* side = (nseg - 2 >= 2 * slab) ? side_stream() : nullptr;

@@ -222,12 +222,10 @@ bppsa_status bppsa_reduce_h128(int T, int B, int t_min, int S, int seg_begin, in
                                const float* Jt, float* tot, hipStream_t s) {
   if (seg_count <= 0) return BPPSA_OK;
   const size_t lds = (size_t)2 * H * LS * sizeof(float);
-  static bool attr_set = false;
-  if (!attr_set) {
-    BPPSA_HIP_TRY(hipFuncSetAttribute((const void*)reduce_h128_kernel,
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    attr_set = true;
-  }
+  // set on every call: the attribute belongs to the current device's copy of the kernel, and the
+  // library keeps no per-process record of which devices it has run on
+  BPPSA_HIP_TRY(hipFuncSetAttribute((const void*)reduce_h128_kernel,
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
   reduce_h128_kernel<<<dim3(seg_count, B), kThreads, lds, s>>>(T, B, t_min, S, seg_begin, Jt, tot);
   BPPSA_CHECK_LAUNCH();
   return BPPSA_OK;
