@@ -134,6 +134,23 @@ bppsa_status bppsa_scan(int T, int B, int H,
                         void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * bppsa_scan for callers that cannot allocate device memory or pass a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments, results and kernels as bppsa_scan, but the scratch
+ * is a fixed array of BPPSA_SCAN_STATIC_SCRATCH_BYTES inside the library (one copy
+ * per GPU, held until the process ends); the call allocates nothing and frees
+ * nothing.  Sizes whose bppsa_scan_workspace_bytes exceeds that maximum are
+ * rejected with BPPSA_EWORKSPACE and nothing is launched (T = 1000, B = 16, H = 20
+ * needs 0.9 MiB; T * B up to about 70 000 fits at H = 20).  Every call on a GPU
+ * shares that GPU's array: calls must be ordered on one stream; calls that overlap
+ * on one GPU race.  What has to start at zero is cleared by the call itself.
+ */
+#define BPPSA_SCAN_STATIC_SCRATCH_BYTES (4u << 20)
+bppsa_status bppsa_scan_static(int T, int B, int H,
+                               const float* Jt, const float* seed,
+                               float* G, float* g0, void* stream);
+
+/*
  * bppsa_build_jacobians + bppsa_scan in one pass for the tanh RNN: the transposed
  * Jacobians of Section 4.1, Jt[t][i][j] = W_hh[j][i] (1 - h[t+1][j]^2), are generated
  * inside the scan kernel from h [T+1,B,H] and w_hh [H,H] and never stored, so neither

@@ -44,6 +44,8 @@ def _load():
     lib.bppsa_scan_workspace_bytes.argtypes = [c_int] * 3
     lib.bppsa_scan.restype = c_int
     lib.bppsa_scan.argtypes = [c_int] * 3 + [c_void_p] * 5 + [c_size_t, c_void_p]
+    lib.bppsa_scan_static.restype = c_int
+    lib.bppsa_scan_static.argtypes = [c_int] * 3 + [c_void_p] * 5
     lib.bppsa_rnn_scan_fused.restype = c_int
     lib.bppsa_rnn_scan_fused.argtypes = [c_int] * 3 + [c_void_p] * 6 + [c_size_t, c_void_p]
     lib.bppsa_param_grads_workspace_bytes.restype = c_size_t
@@ -184,6 +186,15 @@ def scan(Jt, seed, G=None, g0=None, workspace=None, stream=None):
     _check(_lib.bppsa_scan(T, B, H, _ptr(Jt), _ptr(seed), _ptr(G), _ptr(g0),
                            workspace.data_ptr(), workspace.numel() * workspace.element_size(),
                            _stream(stream)), "bppsa_scan")
+    return G
+
+
+def scan_static(Jt, seed, G, g0=None, stream=None):
+    """bppsa_scan_static: bppsa_scan on the library's fixed scratch array; allocates nothing,
+    so G (and g0) must be passed in."""
+    T, B, H, _ = Jt.shape
+    _check(_lib.bppsa_scan_static(T, B, H, _ptr(Jt), _ptr(seed), _ptr(G), _ptr(g0), _stream(stream)),
+           "bppsa_scan_static")
     return G
 
 

@@ -1,9 +1,33 @@
 // bppsa_scan entry point: validation, workspace accounting and kernel choice.
+#include <mutex>
+
 #include "bppsa_internal.h"
 #include "scan_plan.h"
 
 namespace {
 constexpr int kMaxGenericH = 128;  // two H x H fp32 tiles must fit the 160 KB LDS
+
+// Scratch of bppsa_scan_static: a fixed array inside the library's code object, so each GPU the
+// library runs on holds its own copy until the process ends.  In host code the name is only a
+// handle; the device address of the current GPU's copy comes from hipGetSymbolAddress.
+constexpr size_t kStaticScratchBytes = BPPSA_SCAN_STATIC_SCRATCH_BYTES;
+__device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+// Device address of `scratch` on the current device; looked up once per device.
+void* static_scratch() {
+  constexpr int kMaxDevices = 64;
+  static void* table[kMaxDevices];
+  static std::mutex lock;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> hold(lock);
+  if (!table[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+    table[dev] = ptr;
+  }
+  return table[dev];
+}
 
 size_t scan_ws_bytes(int T, int B, int H) {
   const size_t a = bppsa_generic_scan_ws(T, B, H, 0);
@@ -37,6 +61,19 @@ extern "C" bppsa_status bppsa_scan(int T, int B, int H,
   if (workspace && ((uintptr_t)workspace & 255)) return BPPSA_EINVAL;
   if (H == 20) return bppsa_scan_h20(T, B, Jt, seed, G, g0, workspace, (hipStream_t)stream);
   return bppsa_scan_generic(T, B, H, Jt, seed, G, g0, workspace, (hipStream_t)stream);
+}
+
+extern "C" bppsa_status bppsa_scan_static(int T, int B, int H, const float* Jt, const float* seed,
+                                          float* G, float* g0, void* stream) {
+  if (T < 1 || B < 1 || H < 1) return BPPSA_EINVAL;
+  if (!Jt || !seed || !G) return BPPSA_EINVAL;
+  if (bppsa_mul_overflows(T, B, H, H)) return BPPSA_EOVERFLOW;
+  if (B > 65535) return BPPSA_ESHAPE;
+  if (H > kMaxGenericH) return BPPSA_EUNSUPPORTED;
+  if (scan_ws_bytes(T, B, H) > kStaticScratchBytes) return BPPSA_EWORKSPACE;   // beyond the fixed maximum
+  void* ws = static_scratch();
+  if (!ws) return BPPSA_EHIP;
+  return bppsa_scan(T, B, H, Jt, seed, G, g0, ws, kStaticScratchBytes, stream);
 }
 
 extern "C" bppsa_status bppsa_rnn_scan_fused(int T, int B, int H, const float* h, const float* w_hh,
