@@ -113,8 +113,8 @@ size_t bppsa_scan_workspace_bytes(int T, int B, int H);
  * Values follow any bracketing of the products (Section 3.5): results agree
  * with sequential back-propagation up to fp32 rounding order; repeated calls
  * on the same inputs return the same bits.
- * Kernels: H = 20 runs as one pass over Jt (segments of 32 steps resident in
- * LDS, Algorithm 1 inside a segment, look-back across segments); H = 128 and
+ * Kernels: H = 20 runs as one pass over Jt (units of 32 or 64 steps held in LDS
+ * and registers, Algorithm 1 inside a unit, look-back across units); H = 128 and
  * every other H <= 128 run the hybrid of Section 5.3 (segment totals, scan of
  * the totals, matrix-vector down-sweep); H > 128 yields BPPSA_EUNSUPPORTED.
  * For long chains at H = 128 the matrix-vector kernels are enqueued on a second
@@ -308,6 +308,23 @@ bppsa_status bppsa_spscan(int n, const bppsa_csr* Jt, const float* seed, float* 
 /* ------------------------------------------------------------------------
  * Measurement aid (not part of the method).
  * ---------------------------------------------------------------------- */
+
+/*
+ * bppsa_scan at H = 20 with its two internal choices exposed, for tests and for measurement; the
+ * gradients are those of bppsa_scan (same kernels, same workspace size).
+ *   absent_dies : bit mask (0..255) of compute dies whose workgroups stand aside, as if the
+ *                 dispatcher had placed no workgroup there; their chains are then picked up by
+ *                 the placement-independent path.  0 = normal operation.
+ *   unit_halves : 0 = chosen from the sizes as bppsa_scan does; 1 or 2 = units of one or two
+ *                 halves of 32 steps regardless of the sizes.
+ *   lookback_stats : NULL, or device memory for three int64: the number of unit totals all
+ *                 look-backs applied (matrix-vector hops), the number of look-backs, and the most
+ *                 hops one look-back took.
+ */
+bppsa_status bppsa_scan_h20_diag(int T, int B, const float* Jt, const float* seed,
+                                 float* G, float* g0,
+                                 void* workspace, size_t workspace_bytes, void* stream,
+                                 int absent_dies, int unit_halves, int64_t* lookback_stats);
 
 /*
  * Plain streaming copy dst[i] = src[i] of n fp32 values (n a multiple of 4,

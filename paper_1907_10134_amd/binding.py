@@ -24,13 +24,13 @@ class BppsaError(RuntimeError):
         super().__init__("%s failed: %s" % (where, _lib.bppsa_strerror(code).decode()))
 
 
-def _load():
-    if not os.path.exists(_LIB_PATH):
+def _load(path=_LIB_PATH):
+    if not os.path.exists(path):
         raise ImportError(
             "libbppsa.so is not built (expected at %s); run "
             "`python -c 'import __graft_entry__ as g; g.build()'` first - there is no "
-            "CPU fallback" % _LIB_PATH)
-    lib = ctypes.CDLL(_LIB_PATH)
+            "CPU fallback" % path)
+    lib = ctypes.CDLL(path)
     c_int, c_void_p, c_size_t = ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t
     lib.bppsa_strerror.restype = ctypes.c_char_p
     lib.bppsa_strerror.argtypes = [c_int]
@@ -44,6 +44,8 @@ def _load():
     lib.bppsa_scan_workspace_bytes.argtypes = [c_int] * 3
     lib.bppsa_scan.restype = c_int
     lib.bppsa_scan.argtypes = [c_int] * 3 + [c_void_p] * 5 + [c_size_t, c_void_p]
+    lib.bppsa_scan_h20_diag.restype = c_int
+    lib.bppsa_scan_h20_diag.argtypes = [c_int] * 2 + [c_void_p] * 5 + [c_size_t, c_void_p, c_int, c_int, c_void_p]
     lib.bppsa_scan_static.restype = c_int
     lib.bppsa_scan_static.argtypes = [c_int] * 3 + [c_void_p] * 5
     lib.bppsa_rnn_scan_fused.restype = c_int
@@ -186,6 +188,22 @@ def scan(Jt, seed, G=None, g0=None, workspace=None, stream=None):
     _check(_lib.bppsa_scan(T, B, H, _ptr(Jt), _ptr(seed), _ptr(G), _ptr(g0),
                            workspace.data_ptr(), workspace.numel() * workspace.element_size(),
                            _stream(stream)), "bppsa_scan")
+    return G
+
+
+def scan_h20_diag(Jt, seed, G=None, g0=None, workspace=None, stream=None, absent_dies=0, unit_halves=0,
+                  lookback_stats=None):
+    """bppsa_scan_h20_diag: the H = 20 scan with chosen dies standing aside / a forced unit length;
+    lookback_stats, if given, is an int64 tensor of 3 that receives (hops, look-backs, max hops)."""
+    T, B, H, _ = Jt.shape
+    if G is None:
+        G = torch.empty((T, B, H), dtype=torch.float32, device=Jt.device)
+    if workspace is None:
+        workspace = _workspace(scan_workspace_bytes(T, B, H), Jt.device)
+    _check(_lib.bppsa_scan_h20_diag(T, B, _ptr(Jt), _ptr(seed), _ptr(G), _ptr(g0), workspace.data_ptr(),
+                                    workspace.numel() * workspace.element_size(), _stream(stream),
+                                    int(absent_dies), int(unit_halves), _ptr(lookback_stats, torch.int64)),
+           "bppsa_scan_h20_diag")
     return G
 
 

@@ -63,6 +63,23 @@ extern "C" bppsa_status bppsa_scan(int T, int B, int H,
   return bppsa_scan_generic(T, B, H, Jt, seed, G, g0, workspace, (hipStream_t)stream);
 }
 
+extern "C" bppsa_status bppsa_scan_h20_diag(int T, int B, const float* Jt, const float* seed, float* G, float* g0,
+                                            void* workspace, size_t workspace_bytes, void* stream,
+                                            int absent_dies, int unit_halves, int64_t* lookback_stats) {
+  if (T < 1 || B < 1) return BPPSA_EINVAL;
+  if (!Jt || !seed || !G) return BPPSA_EINVAL;
+  if (bppsa_mul_overflows(T, B, 20, 20)) return BPPSA_EOVERFLOW;
+  if (unit_halves < 0 || unit_halves > 2 || absent_dies < 0 || absent_dies > 0xff) return BPPSA_EINVAL;
+  const size_t need = scan_ws_bytes(T, B, 20);
+  if (!workspace || workspace_bytes < need) return BPPSA_EWORKSPACE;
+  if ((uintptr_t)workspace & 255) return BPPSA_EINVAL;
+  bppsa_status st = bppsa_scan_h20(T, B, Jt, seed, G, g0, workspace, (hipStream_t)stream, nullptr, nullptr,
+                                   absent_dies, unit_halves);
+  if (st != BPPSA_OK || !lookback_stats) return st;
+  return bppsa_scan_h20_hops(T, B, g0 != nullptr, unit_halves, workspace,
+                             reinterpret_cast<long long*>(lookback_stats), (hipStream_t)stream);
+}
+
 extern "C" bppsa_status bppsa_scan_static(int T, int B, int H, const float* Jt, const float* seed,
                                           float* G, float* g0, void* stream) {
   if (T < 1 || B < 1 || H < 1) return BPPSA_EINVAL;

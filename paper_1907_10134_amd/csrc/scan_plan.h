@@ -33,17 +33,23 @@ static inline size_t bppsa_generic_scan_ws(int T, int B, int H, int want_g0) {
 #define BPPSA_H20_INC_STRIDE 32    /* floats: a 20-vector padded to one cache line */
 #define BPPSA_H20_HEADER_BYTES 4096
 
-// Workspace of the single-pass scan: header, one status word, one published total and one
-// published inclusive vector per (segment, sample), and the transposed weights of the fused form.
+// Workspace of the single-pass scan: header, one status word and one hop count per (unit,
+// sample), one published total and one published inclusive vector per (unit, sample), and the
+// transposed weights of the fused form.  Sized for units of one half (the larger case).
 static inline size_t bppsa_h20_scan_ws(int T, int B) {
   const size_t nblk = (size_t)bppsa_ceil_div(T, BPPSA_H20_SEGMENT) * B;
-  return BPPSA_H20_HEADER_BYTES + bppsa_align_up(nblk * sizeof(int), 256) +
+  return BPPSA_H20_HEADER_BYTES + 2 * bppsa_align_up(nblk * sizeof(int), 256) +
          nblk * (BPPSA_H20_AGG_STRIDE + BPPSA_H20_INC_STRIDE) * sizeof(float) + 20 * 20 * sizeof(float);
 }
 
+// skip_dies (bit mask of compute dies whose workgroups stand aside) and unit_halves (0 = chosen
+// from the sizes, 1 or 2 = forced) are 0 except in the diagnostic call.
 bppsa_status bppsa_scan_h20(int T, int B, const float* Jt, const float* seed, float* G, float* g0,
                             void* workspace, hipStream_t stream, const float* h = nullptr,
-                            const float* w_hh = nullptr);
+                            const float* w_hh = nullptr, int skip_dies = 0, int unit_halves = 0);
+
+bppsa_status bppsa_scan_h20_hops(int T, int B, int want_g0, int unit_halves, const void* workspace,
+                                 long long* out, hipStream_t stream);
 
 bppsa_status bppsa_scan_generic(int T, int B, int H, const float* Jt, const float* seed,
                                 float* G, float* g0, void* workspace, hipStream_t stream);

@@ -169,21 +169,56 @@ def test_end_to_end_norm_preserving(bp, T):
         assert rel_err(got, ref) <= TOL
 
 
+def _ws(bp, T, B, H=20, fill=0xC3):
+    import torch
+    return torch.full((bp.scan_workspace_bytes(T, B, H),), fill, dtype=torch.uint8, device="cuda")
+
+
+def _error_word(ws):
+    import torch
+    return int(ws[:4].view(torch.int32).item())
+
+
+@pytest.mark.parametrize("T,B,H", [s for s in SCAN_SHAPES if s[2] == 20] +
+                         [(2500, 16, 20), (64, 8, 20), (129, 8, 20), (2049, 3, 20), (5000, 8, 20), (3000, 12, 20)])
+@pytest.mark.parametrize("want_g0", [False, True])
+def test_scan_h20_units_of_two_halves_match_linear_scan(bp, T, B, H, want_g0):
+    """The form of the H=20 scan that long chains take (units of 64 steps, the first half parked
+    in registers), forced on every shape: chain lengths around multiples of 32 and 64, one unit
+    only, batch sizes on and off the die-local path."""
+    import torch
+    if T >= 1000:
+        jt, seed = workloads.reflection_jacobian_chain(T, B, H, seed=T * 131 + H)
+    else:
+        jt, seed = workloads.random_jacobian_chain(T, B, H, seed=T * 131 + H, scale=1.05 / np.sqrt(H))
+    G_ref, g0_ref = oscan.linear_scan(jt, seed)
+    g0 = torch.empty((B, H), dtype=torch.float32, device="cuda") if want_g0 else None
+    ws = _ws(bp, T, B)
+    G = bp.scan_h20_diag(to_gpu(jt), to_gpu(seed), g0=g0, workspace=ws, unit_halves=2)
+    torch.cuda.synchronize()
+    assert _error_word(ws) == 0
+    assert rel_err(to_np(G), G_ref) <= TOL
+    assert per_step_err(to_np(G), G_ref) <= 20 * TOL
+    assert np.array_equal(to_np(G[T - 1]), seed)
+    if want_g0:
+        assert rel_err(to_np(g0), g0_ref) <= TOL * max(1.0, np.max(np.abs(G_ref)) / np.max(np.abs(g0_ref)))
+
+
+@pytest.mark.parametrize("halves", [1, 2])
 @pytest.mark.parametrize("mask", [0x01, 0xA5, 0xFF])
-def test_scan_h20_fallback_when_dies_stand_aside(bp, mask, monkeypatch):
+def test_scan_h20_fallback_when_dies_stand_aside(bp, mask, halves):
     """Chains whose compute die takes no part are picked up by the last workgroup (device-scope path)."""
     import torch
     T, B, H = 200, 16, 20
     jt, seed = workloads.random_jacobian_chain(T, B, H, seed=77, scale=1.05 / np.sqrt(H))
     G_ref, _ = oscan.linear_scan(jt, seed)
     djt, dseed = to_gpu(jt), to_gpu(seed)
-    G_normal = to_np(bp.scan(djt, dseed))
-    monkeypatch.setenv("BPPSA_H20_SKIP_DIES", str(mask))
-    ws = torch.zeros(bp.scan_workspace_bytes(T, B, H), dtype=torch.uint8, device="cuda")
-    G = to_np(bp.scan(djt, dseed, workspace=ws))
+    ws0 = _ws(bp, T, B)
+    G_normal = to_np(bp.scan_h20_diag(djt, dseed, workspace=ws0, unit_halves=halves))
+    ws = _ws(bp, T, B, fill=0)
+    G = to_np(bp.scan_h20_diag(djt, dseed, workspace=ws, absent_dies=mask, unit_halves=halves))
     torch.cuda.synchronize()
-    monkeypatch.delenv("BPPSA_H20_SKIP_DIES")
-    assert int(ws[:4].view(torch.int32).item()) == 0          # no bounded wait expired
+    assert _error_word(ws0) == 0 and _error_word(ws) == 0     # no bounded wait expired
     assert rel_err(G, G_ref) <= TOL
     assert np.array_equal(G, G_normal)                        # same bits as the die-local path
 
