@@ -404,11 +404,19 @@ __device__ __forceinline__ void up_sweep_upper(float* mat, int role, int slot, i
     wave_product(sub + toff(7), sub + toff(3), slot, q);
   }
   __syncthreads();
-  if (role >= 2) wave_product(mat + toff(16 * (role - 2) + 15), mat + toff(16 * (role - 2) + 7), slot, q);
+  // levels 3 and 4 (and the unit total) keep one or two waves busy while the others wait for
+  // them: those waves run at a raised priority
+  if (role >= 2) {
+    __builtin_amdgcn_s_setprio(2);
+    wave_product(mat + toff(16 * (role - 2) + 15), mat + toff(16 * (role - 2) + 7), slot, q);
+    __builtin_amdgcn_s_setprio(0);
+  }
   __syncthreads();
   if (role == 1) {
+    __builtin_amdgcn_s_setprio(2);
     wave_product(mat + toff(31), mat + toff(15), slot, q);
     if (lo) wave_product(mat + toff(31), lo, slot, q);
+    __builtin_amdgcn_s_setprio(0);
   }
   __syncthreads();
 }
