@@ -45,6 +45,34 @@ def scan_algorithmic_bytes(T, B, H):
     return T * B * (4 * H * H + 4 * H) + 4 * B * H
 
 
+def scan_h20_work(T, B, want_g0, hops, resident=768):
+    """Products the H=20 scan executes for these sizes: matrix-matrix (2 H^3 FLOP each) and
+    matrix-vector (2 H^2 FLOP each).  A unit is one or two halves of 32 steps; every half costs the
+    31 products of Algorithm 1's up-sweep on 32 elements, a two-half unit one more for its total;
+    the down-sweep is one matrix-vector product per element plus the few of the levels above a
+    wave's eight elements that the waves repeat, the unit's outgoing vector and, for two halves,
+    the vector between them; `hops` (measured) is the number of totals all look-backs applied."""
+    n = T if want_g0 else T - 1
+    halves = 2 if -(-n // 32) * B > resident else 1
+    nunit = -(-n // (32 * halves))
+    mm = nunit * B * (31 * halves + (1 if halves == 2 else 0))
+    per_half_mv = 28 + 4          # seven per wave and sub-tree, plus the entering vectors of the four sub-trees
+    mv = nunit * B * (per_half_mv * halves + 1 + (1 if halves == 2 else 0)) + int(hops)
+    return {"unit_steps": 32 * halves, "units": nunit * B, "matrix_matrix": mm, "matrix_vector": mv,
+            "flop": mm * 2 * 20 ** 3 + mv * 2 * 20 ** 2}
+
+
+def lookback_hops(bp, b):
+    """Hops (unit totals applied) of all look-backs of one scan of this workload, measured."""
+    import torch
+    stats = torch.zeros(3, dtype=torch.int64, device="cuda")
+    bp.scan_h20_diag(b["Jt"], b["seed"], G=b["G"], workspace=b["scan_ws"], lookback_stats=stats)
+    torch.cuda.synchronize()
+    assert int(b["scan_ws"][:4].view(torch.int32).item()) == 0, "a bounded wait inside the scan expired"
+    hops, count, most = (int(v) for v in stats.cpu())
+    return {"total": hops, "lookbacks": count, "mean": round(hops / max(count, 1), 2), "max": most}
+
+
 def prepare(bp, w):
     """Upload a workload and run the (untimed) forward pass and head on the GPU."""
     import torch
@@ -177,10 +205,14 @@ def long_scan(bp, workloads, steps, fused=True):
     fused_ms = time_fused(bp, b2, max(5, min(50, steps)), 50)[1] if fused else None
     nbytes = scan_algorithmic_bytes(w2["T"], w2["B"], w2["H"])
     gbps = nbytes / (ms * 1e-3) / 1e9
+    hops = lookback_hops(bp, b2)
+    work = scan_h20_work(w2["T"], w2["B"], False, hops["total"])
     return {"workload": "rnn_tanh_H20_I1_T30000_B16 (configs[2])", "scan_ms": round(ms, 5),
             "algorithmic_bytes": nbytes, "gbps": round(gbps, 2),
             "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 5),
             "traffic": measured_traffic_bytes(w2["T"], w2["B"], w2["H"]),
+            "products": work, "gflops": round(work["flop"] / (ms * 1e-3) / 1e9, 1),
+            "lookback_hops": hops,
             "fused_scan_ms": None if fused_ms is None else round(fused_ms, 5)}
 
 
@@ -346,6 +378,18 @@ def cpu_baseline(w, budget_s=15.0):
     return statistics.median(times), len(times)
 
 
+def host_cpu():
+    model = "unknown"
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                model = line.split(":", 1)[1].strip()
+                break
+    except OSError:
+        pass
+    return {"nproc": os.cpu_count(), "model": model}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -353,6 +397,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-long", action="store_true", help="skip the T=30000 scan figure")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--no-extra", action="store_true", help="skip the compact GRU (configs[3]) and CNN (configs[4]) figures")
     ap.add_argument("--no-fused", action="store_true",
                     help="skip the bppsa_rnn_scan_fused figures (profiling runs: keeps the kernel's launches uniform)")
     ap.add_argument("--long-only", action="store_true",
@@ -430,6 +475,26 @@ def main():
                      "traffic": measured_traffic_bytes(T, B, H), "algorithmic_bytes": scan_bytes},
     }
 
+    # scan work and look-back statistics of the headline workload, and one roofline entry per call
+    hops1 = lookback_hops(bp, bufs)
+    work1 = scan_h20_work(T, B, False, hops1["total"])
+    out["scan_products"] = work1
+    out["scan_gflops"] = round(work1["flop"] / (parts["scan_ms"] * 1e-3) / 1e9, 1)
+    out["scan_lookback_hops"] = hops1
+    I = w["I"]
+    call_bytes = {
+        "bppsa_build_jacobians": T * B * (4 * H * H + 4 * H) + 4 * H * H,          # tiles written, h and W_hh read
+        "bppsa_scan": scan_bytes,
+        "bppsa_param_grads": T * B * (2 * 4 * H + 4 * H + 4 * I) + 4 * H * (H + I + 1),   # G, h (twice: as h[t] and h[t-1]), x read
+    }
+    out["rooflines"] = []
+    for call, key in (("bppsa_build_jacobians", "build_jacobians_ms"), ("bppsa_scan", "scan_ms"),
+                      ("bppsa_param_grads", "param_grads_ms")):
+        g = call_bytes[call] / (parts[key] * 1e-3) / 1e9
+        out["rooflines"].append({"call": call, "bound": "hbm", "algorithmic_bytes": call_bytes[call],
+                                 "ms": round(parts[key], 5), "achieved": round(g, 1), "peak": HBM_PEAK_GBPS,
+                                 "unit": "GB/s", "frac": round(g / HBM_PEAK_GBPS, 5)})
+
     if not args.no_long:
         del bufs
         torch.cuda.empty_cache()
@@ -440,9 +505,23 @@ def main():
         out["measured_copy_gbps"] = cal["gbps_read_plus_write"]
         out["long_scan"]["frac_of_measured_copy"] = round(out["long_scan"]["gbps"] / cal["gbps_read_plus_write"], 5)
 
+    if not args.no_extra:
+        # the other two workloads, compact: GRU H=128 (scan bound by the fp32 matrix cores) and the
+        # pruned CNN (sparse scan)
+        torch.cuda.empty_cache()
+        g = gru_workload(bp, workloads, 5)
+        out["gru"] = {k: g[k] for k in ("workload", "build_jacobians_ms", "scan_ms", "param_grads_ms",
+                                        "scan_tflops", "frac_of_fp32_mfma_peak")}
+        torch.cuda.empty_cache()
+        c = cnn_workload(bp, workloads, 10)
+        out["cnn"] = {"workload": c["workload"], "nnz": c["nnz"], "build_all_jacobians_ms": c["build_all_jacobians_ms"],
+                      "up_levels_0": c["up_levels_0"], "up_levels_2": c["up_levels_2"],
+                      "spmv_chain_gbps": c["spmv_chain_gbps"]}
+        torch.cuda.empty_cache()
+
     if not args.no_cpu:
         ms, reps = cpu_baseline(w)
-        out["cpu_baseline"] = {"value": round(ms, 4), "unit": "ms", "cores": 1, "kind": "oracle",
+        out["cpu_baseline"] = {"value": round(ms, 4), "unit": "ms", "cores": 1, "kind": "oracle", **host_cpu(),
                                "sample": "full configs[1] workload (T=1000, B=16): fp64 sequential chain + "
                                          "parameter sums, median of %d passes, numpy limited to one thread" % reps}
     print(json.dumps(out))

@@ -71,16 +71,31 @@ rnn_jacobians_h20_kernel(int tiles, int B, const float* __restrict__ h, const fl
 #pragma unroll
   for (int u = 0; u < 4; ++u) w[u] = w_hh[(j4 + u) * H + i];
   const int step = gridDim.x * kH20TilesPerPass;
-  for (int m = blockIdx.x * kH20TilesPerPass + slot; m < tiles; m += step) {
-    const bj_v4f hv = *reinterpret_cast<const bj_v4f*>(h + (size_t)(m + B) * H + j4);   // h[t+1][b][j4..]
-    // 1 - h^2 as one fused multiply-add, spelled out: the fused scan forms the same tile and
-    // must get the same bits whatever the compiler would contract
-    bj_v4f o;
+  // Four tiles per trip: the four 16-byte reads of h are issued before the first result is
+  // formed, so a thread waits for memory once per four stores instead of once per store.
+  constexpr int kTrip = 4;
+  for (int m0 = blockIdx.x * kH20TilesPerPass + slot; m0 < tiles; m0 += kTrip * step) {
+    bj_v4f hv[kTrip];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) o[u] = w[u] * __builtin_fmaf(-hv[u], hv[u], 1.0f);
-    bj_v4f* dst = reinterpret_cast<bj_v4f*>(Jt + (size_t)m * H * H + p * 4);
-    if (STREAM) __builtin_nontemporal_store(o, dst);   // far larger than the caches: do not allocate
-    else *dst = o;                                     // small enough to be read back from cache
+    for (int u = 0; u < kTrip; ++u) {
+      const int m = m0 + u * step;
+      hv[u] = bj_v4f{0.f, 0.f, 0.f, 0.f};
+      if (m < tiles) hv[u] = *reinterpret_cast<const bj_v4f*>(h + (size_t)(m + B) * H + j4);   // h[t+1][b][j4..]
+    }
+#pragma unroll
+    for (int u = 0; u < kTrip; ++u) {
+      const int m = m0 + u * step;
+      if (m < tiles) {
+        // 1 - h^2 as one fused multiply-add, spelled out: the fused scan forms the same tile and
+        // must get the same bits whatever the compiler would contract
+        bj_v4f o;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) o[c] = w[c] * __builtin_fmaf(-hv[u][c], hv[u][c], 1.0f);
+        bj_v4f* dst = reinterpret_cast<bj_v4f*>(Jt + (size_t)m * H * H + p * 4);
+        if (STREAM) __builtin_nontemporal_store(o, dst);   // far larger than the caches: do not allocate
+        else *dst = o;                                     // small enough to be read back from cache
+      }
+    }
   }
 }
 

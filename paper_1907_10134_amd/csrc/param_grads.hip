@@ -148,27 +148,45 @@ rnn_param_partials_h20_kernel(long long rows, int B, int I, int rows_per_block,
   }
 }
 
-// One wave per output element: lanes add the per-block partials in a fixed
-// strided order, then the wave reduces (deterministic).
-__global__ void __launch_bounds__(256)
+// Adds the per-block partials in a fixed order (deterministic).  A workgroup owns 64 consecutive
+// output elements; its sixteen waves each add every sixteenth block's partial for them -
+// consecutive lanes read consecutive addresses, sixteen independent loads in flight per thread -
+// and the sixteen sums are added in wave order.
+constexpr int kFinishWaves = 16;
+__global__ void __launch_bounds__(64 * kFinishWaves)
 rnn_param_finish_kernel(int nblocks, int H, int I, const float* __restrict__ part,
                         float* __restrict__ dW_ih, float* __restrict__ dW_hh,
                         float* __restrict__ db_ih, float* __restrict__ db_hh) {
+  __shared__ float red[kFinishWaves][64];
   const int W = H + I + 1;
   const int E = H * W;
-  const int lane = threadIdx.x & 63;
-  const int e = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
-  if (e >= E) return;                       // whole wave leaves together
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int e = blockIdx.x * 64 + lane;
   float s = 0.f;
-  for (int k = lane; k < nblocks; k += 64) s += part[(size_t)k * E + e];
-  for (int m = 32; m >= 1; m >>= 1) s += __shfl_xor(s, m);
-  if (lane != 0) return;
+  if (e < E) {
+    for (int k0 = wave; k0 < nblocks; k0 += 16 * kFinishWaves) {
+      float v[16];
+#pragma unroll
+      for (int u = 0; u < 16; ++u) {
+        const int k = k0 + u * kFinishWaves;
+        v[u] = k < nblocks ? part[(size_t)k * E + e] : 0.f;
+      }
+#pragma unroll
+      for (int u = 0; u < 16; ++u) s += v[u];
+    }
+  }
+  red[wave][lane] = s;
+  __syncthreads();
+  if (wave != 0 || e >= E) return;
+  float t = red[0][lane];
+#pragma unroll
+  for (int w = 1; w < kFinishWaves; ++w) t += red[w][lane];
   const int i = e / W, c = e - i * W;
-  if (c < H) dW_hh[(size_t)i * H + c] = s;
-  else if (c < H + I) dW_ih[(size_t)i * I + (c - H)] = s;
+  if (c < H) dW_hh[(size_t)i * H + c] = t;
+  else if (c < H + I) dW_ih[(size_t)i * I + (c - H)] = t;
   else {
-    db_ih[i] = s;
-    if (db_hh) db_hh[i] = s;
+    db_ih[i] = t;
+    if (db_hh) db_hh[i] = t;
   }
 }
 
@@ -242,7 +260,7 @@ extern "C" bppsa_status bppsa_param_grads(int cell, int T, int B, int H, int I,
   }
   BPPSA_CHECK_LAUNCH();
   // blocks past the last row range wrote zeros, so summing all nb partials is exact
-  rnn_param_finish_kernel<<<bppsa_ceil_div(E, 4), 256, 0, s>>>(nb, H, I, part, dW_ih, dW_hh, db_ih, db_hh);
+  rnn_param_finish_kernel<<<bppsa_ceil_div(E, 64), 64 * kFinishWaves, 0, s>>>(nb, H, I, part, dW_ih, dW_hh, db_ih, db_hh);
   BPPSA_CHECK_LAUNCH();
   return BPPSA_OK;
 }
