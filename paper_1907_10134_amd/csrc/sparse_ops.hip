@@ -4,7 +4,7 @@
 // nodes, split into a symbolic phase (row lengths, then ascending column
 // indices, both from a per-row bitmap of B's columns held in LDS) and a numeric
 // phase, so that the symbolic work can be done once ahead of the training loop
-// (Section 4.3).
+// (Section 4.3).  The numeric phase adds the terms of every value in a fixed order.
 #include "bppsa_internal.h"
 #include "sparse_common.h"
 
@@ -162,128 +162,244 @@ spgemm_symbolic_kernel(int words, const int32_t* __restrict__ a_indptr,
   }
 }
 
-// C's row is owned by one workgroup and accumulated in 48 KB of LDS (three workgroups per
-// compute unit):
-//   DENSE  - B has at most kNumericCap columns: one accumulator per column, products are
-//            added at acc[col] with LDS atomics and the row's entries are gathered at the end;
-//   !DENSE - rows of up to kNumericCap / 2 entries stage their (ascending) column indices in
-//            LDS, every product finds its slot by binary search there; longer rows take the
-//            same steps directly in global memory.
-constexpr int kNumericCap = 12288;
+// ---- numeric phase of C = A B for a known structure ---------------------------------------------
+// Every value of C is formed by ONE wave, which adds the terms of an entry in a fixed order
+// (entries of A's row in storage order), so the values are the same bits on every run; no two
+// waves ever add to the same accumulator.  Three kernels, chosen once per product when the plan
+// is built:
+//
+//   single : every entry of C is exactly one product a * b (the number of multiply-adds equals
+//            nnz(C): a diagonal or selection matrix on either side, i.e. every product with a ReLU
+//            or pooling Jacobian).  Nothing is summed; one wave per row writes the products to
+//            their places.
+//   wave   : rows of C of up to kWaveRowCap entries: one wave per row stages the row's column
+//            indices in LDS, walks A's row and adds each term at the slot found by binary search.
+//   block  : longer rows: one workgroup per row.  The columns are cut into four equal ranges, one
+//            per wave, and a table built with the plan says where each row of B crosses those
+//            boundaries, so a wave reads exactly its share of every row of B and owns its share of
+//            the accumulators: one per column when B has at most kBlockDenseCols columns, else
+//            the row's entries staged in LDS (up to kBlockStagedCap) or left in global memory.
+constexpr int kWaveRowCap = 1024;
+constexpr int kBlockDenseCols = 12288;
+constexpr int kBlockStagedCap = 6144;
 
-template <bool DENSE>
+// first position in sorted idx[0..n) whose value is >= col
+__device__ __forceinline__ int lower_bound_i32(const int32_t* idx, int n, int col) {
+  int lo = 0, hi = n;
+  while (lo < hi) {
+    const int mid = (lo + hi) >> 1;
+    if (idx[mid] < col) lo = mid + 1; else hi = mid;
+  }
+  return lo;
+}
+
+// split[3 k + j] = first entry of row k of B whose column is >= (j + 1) * ceil(cols / 4)
 __global__ void __launch_bounds__(256)
-spgemm_numeric_kernel(int b_cols, const int32_t* __restrict__ a_indptr, const int32_t* __restrict__ a_indices,
-                      const float* __restrict__ a_data, const int32_t* __restrict__ b_indptr,
-                      const int32_t* __restrict__ b_indices, const float* __restrict__ b_data,
-                      const int32_t* __restrict__ c_indptr, const int32_t* __restrict__ c_indices,
-                      float* __restrict__ c_data) {
-  __shared__ float lds[kNumericCap];
+row_splits_kernel(int rows, int cols, const int32_t* __restrict__ indptr, const int32_t* __restrict__ indices,
+                  int32_t* __restrict__ split) {
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= 3 * rows) return;
+  const int k = t / 3, j = t - 3 * k;
+  const int quarter = (cols + 3) / 4;
+  const int s = indptr[k], e = indptr[k + 1];
+  split[t] = s + lower_bound_i32(indices + s, e - s, (j + 1) * quarter);
+}
+
+__global__ void __launch_bounds__(256)
+spgemm_numeric_single_kernel(int rows, const int32_t* __restrict__ a_indptr, const int32_t* __restrict__ a_indices,
+                             const float* __restrict__ a_data, const int32_t* __restrict__ b_indptr,
+                             const int32_t* __restrict__ b_indices, const float* __restrict__ b_data,
+                             const int32_t* __restrict__ c_indptr, const int32_t* __restrict__ c_indices,
+                             float* __restrict__ c_data) {
+  const int lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const int cs = c_indptr[row], n = c_indptr[row + 1] - cs;
+  if (n == 0) return;
+  const int as = a_indptr[row], ae = a_indptr[row + 1];
+  if (ae - as == 1) {                            // the row of C is a scaled copy of one row of B
+    const int k = a_indices[as];
+    const float av = a_data[as];
+    const int bs = b_indptr[k];
+    for (int j = lane; j < n; j += 64) c_data[cs + j] = av * b_data[bs + j];
+    return;
+  }
+  // one lane per entry of A's row; its (short) row of B goes to the places found by binary search
+  for (int p = as + lane; p < ae; p += 64) {
+    const int k = a_indices[p];
+    const float av = a_data[p];
+    const int bs = b_indptr[k], be = b_indptr[k + 1];
+    for (int q = bs; q < be; ++q) {
+      const int slot = lower_bound_i32(c_indices + cs, n, b_indices[q]);
+      c_data[cs + slot] = av * b_data[q];
+    }
+  }
+}
+
+__global__ void __launch_bounds__(256)
+spgemm_numeric_wave_kernel(int rows, const int32_t* __restrict__ a_indptr, const int32_t* __restrict__ a_indices,
+                           const float* __restrict__ a_data, const int32_t* __restrict__ b_indptr,
+                           const int32_t* __restrict__ b_indices, const float* __restrict__ b_data,
+                           const int32_t* __restrict__ c_indptr, const int32_t* __restrict__ c_indices,
+                           float* __restrict__ c_data) {
+  __shared__ int32_t cidx_s[4][kWaveRowCap];
+  __shared__ float acc_s[4][kWaveRowCap];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int row = blockIdx.x * 4 + wave;
+  if (row >= rows) return;                       // no workgroup barrier below: waves are independent
+  int32_t* cidx = cidx_s[wave];
+  float* acc = acc_s[wave];
+  const int cs = c_indptr[row], n = c_indptr[row + 1] - cs;
+  if (n == 0) return;
+  const int as = a_indptr[row], ae = a_indptr[row + 1];
+  for (int j = lane; j < n; j += 64) {
+    cidx[j] = c_indices[cs + j];
+    acc[j] = 0.f;
+  }
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+  // Entries of A's row in storage order; the entries of one row of B have distinct columns, so
+  // the lanes of one step never meet at a slot, and LDS operations of a wave complete in order.
+  // Each lane first fetches one entry of A's row and the bounds of its row of B; the wave then
+  // takes them four at a time so that the loads of four rows of B are in flight together.
+  for (int p0 = as; p0 < ae; p0 += 64) {
+    const int mine = p0 + lane;
+    int bs_l = 0, be_l = 0;
+    float av_l = 0.f;
+    if (mine < ae) {
+      const int k = a_indices[mine];
+      av_l = a_data[mine];
+      bs_l = b_indptr[k];
+      be_l = b_indptr[k + 1];
+    }
+    const int cnt = (ae - p0 < 64) ? (ae - p0) : 64;
+    for (int e = 0; e < cnt; e += 4) {
+      int bs[4], be[4], col[4];
+      float av[4], bv[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int src = (e + u < cnt) ? e + u : e;
+        bs[u] = __builtin_amdgcn_readlane(bs_l, src);
+        be[u] = (e + u < cnt) ? __builtin_amdgcn_readlane(be_l, src) : bs[u];
+        av[u] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, av_l), src));
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int q = bs[u] + lane;
+        col[u] = (q < be[u]) ? b_indices[q] : -1;
+        bv[u] = (q < be[u]) ? b_data[q] : 0.f;
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        if (col[u] >= 0) acc[lower_bound_i32(cidx, n, col[u])] += av[u] * bv[u];
+        for (int q0 = bs[u] + 64 + lane; q0 < be[u]; q0 += 64)      // a row of B longer than one wave
+          acc[lower_bound_i32(cidx, n, b_indices[q0])] += av[u] * b_data[q0];
+      }
+    }
+  }
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+  for (int j = lane; j < n; j += 64) c_data[cs + j] = acc[j];
+}
+
+// MODE 0: one accumulator per column of B (LDS);  MODE 1: the row's entries staged in LDS, slots by
+// binary search;  MODE 2: the same search on the row in global memory, where the additions are
+// memory-side add operations: all additions to one entry come from one wave, in its program
+// order, so they too are applied in a fixed order.
+template <int MODE>
+__global__ void __launch_bounds__(256)
+spgemm_numeric_block_kernel(int b_cols, const int32_t* __restrict__ a_indptr, const int32_t* __restrict__ a_indices,
+                            const float* __restrict__ a_data, const int32_t* __restrict__ b_indptr,
+                            const int32_t* __restrict__ b_indices, const float* __restrict__ b_data,
+                            const int32_t* __restrict__ b_split, const int32_t* __restrict__ c_indptr,
+                            const int32_t* __restrict__ c_indices, float* __restrict__ c_data) {
+  __shared__ float lds[kBlockDenseCols];
   const int row = blockIdx.x;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwave = blockDim.x >> 6;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int cs = c_indptr[row], ce = c_indptr[row + 1];
   const int n = ce - cs;
   const int as = a_indptr[row], ae = a_indptr[row + 1];
-  if (n == 0) return;
-  if (DENSE) {
+  if (n == 0) return;                            // uniform over the workgroup
+  float* cacc = lds;
+  int32_t* cidx = reinterpret_cast<int32_t*>(lds + kBlockDenseCols / 2);
+  if (MODE == 0) {
     for (int p = threadIdx.x; p < n; p += blockDim.x) lds[c_indices[cs + p]] = 0.f;
-    __syncthreads();
-    // Each lane first fetches one entry of A's row and the bounds of the matching row of B;
-    // the wave then walks those entries four at a time so that the loads of four rows of B are
-    // in flight together (the rows are short, so one row per trip would leave the wave waiting
-    // on memory most of the time).
-    for (int p0 = as + wave * 64; p0 < ae; p0 += nwave * 64) {
-      const int mine = p0 + lane;
-      int bs_l = 0, be_l = 0;
-      float av_l = 0.f;
-      if (mine < ae) {
-        const int k = a_indices[mine];
-        av_l = a_data[mine];
-        bs_l = b_indptr[k];
-        be_l = b_indptr[k + 1];
-      }
-      const int cnt = (ae - p0 < 64) ? (ae - p0) : 64;
-      for (int e = 0; e < cnt; e += 4) {
-        int bs[4], be[4], col[4];
-        float av[4], bv[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          const int src = (e + u < cnt) ? e + u : e;
-          bs[u] = __builtin_amdgcn_readlane(bs_l, src);
-          be[u] = (e + u < cnt) ? __builtin_amdgcn_readlane(be_l, src) : bs[u];
-          av[u] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, av_l), src));
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          const int q = bs[u] + lane;
-          col[u] = (q < be[u]) ? b_indices[q] : -1;
-          bv[u] = (q < be[u]) ? b_data[q] : 0.f;
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u)
-          if (col[u] >= 0) atomicAdd(&lds[col[u]], av[u] * bv[u]);
-        for (int u = 0; u < 4; ++u) {             // rows of B longer than one wave: four loads in flight
-          for (int q0 = bs[u] + 64 + lane; q0 < be[u]; q0 += 256) {
-            int c4[4];
-            float v4[4];
-#pragma unroll
-            for (int w = 0; w < 4; ++w) {
-              const int q = q0 + 64 * w;
-              c4[w] = (q < be[u]) ? b_indices[q] : -1;
-              v4[w] = (q < be[u]) ? b_data[q] : 0.f;
-            }
-#pragma unroll
-            for (int w = 0; w < 4; ++w)
-              if (c4[w] >= 0) atomicAdd(&lds[c4[w]], av[u] * v4[w]);
-          }
-        }
-      }
-    }
-    __syncthreads();
-    for (int p = threadIdx.x; p < n; p += blockDim.x) c_data[cs + p] = lds[c_indices[cs + p]];
-    return;
-  }
-  if (n <= kNumericCap / 2) {
-    float* cacc = lds;
-    int32_t* cidx = reinterpret_cast<int32_t*>(lds + kNumericCap / 2);
+  } else if (MODE == 1) {
     for (int p = threadIdx.x; p < n; p += blockDim.x) {
       cidx[p] = c_indices[cs + p];
       cacc[p] = 0.f;
     }
-    __syncthreads();
-    for (int p = as + wave; p < ae; p += nwave) {
-      const int k = a_indices[p];
-      const float av = a_data[p];
-      const int bs = b_indptr[k], be = b_indptr[k + 1];
-      for (int q = bs + lane; q < be; q += 64) {
-        const int col = b_indices[q];
-        int lo = 0, hi = n - 1;
-        while (lo < hi) {
-          const int mid = (lo + hi) >> 1;
-          if (cidx[mid] < col) lo = mid + 1; else hi = mid;
-        }
-        atomicAdd(&cacc[lo], av * b_data[q]);
-      }
-    }
-    __syncthreads();
-    for (int p = threadIdx.x; p < n; p += blockDim.x) c_data[cs + p] = cacc[p];
-    return;
+  } else {
+    for (int p = cs + threadIdx.x; p < ce; p += blockDim.x) c_data[p] = 0.f;
   }
-  for (int p = cs + threadIdx.x; p < ce; p += blockDim.x) c_data[p] = 0.f;
   __syncthreads();
-  for (int p = as + wave; p < ae; p += nwave) {
-    const int k = a_indices[p];
-    const float av = a_data[p];
-    const int bs = b_indptr[k], be = b_indptr[k + 1];
-    for (int q = bs + lane; q < be; q += 64) {
-      const int col = b_indices[q];
-      int lo = cs, hi = ce - 1;
-      while (lo < hi) {
-        const int mid = (lo + hi) >> 1;
-        if (c_indices[mid] < col) lo = mid + 1; else hi = mid;
-      }
-      atomicAdd(&c_data[lo], av * b_data[q]);
+  // the slots of this wave's column range (MODE 1 and 2): [slot_lo, slot_hi)
+  const int quarter = (b_cols + 3) / 4;
+  int slot_lo = 0, slot_n = n;
+  if (MODE == 1) {
+    slot_lo = lower_bound_i32(cidx, n, wave * quarter);
+    slot_n = lower_bound_i32(cidx, n, (wave + 1) * quarter) - slot_lo;
+  } else if (MODE == 2) {
+    slot_lo = lower_bound_i32(c_indices + cs, n, wave * quarter);
+    slot_n = lower_bound_i32(c_indices + cs, n, (wave + 1) * quarter) - slot_lo;
+  }
+  // Every wave walks all of A's row in storage order but reads only its share of each row of B.
+  // Each lane first fetches one entry of A's row and the bounds of that share; the wave then
+  // takes those entries four at a time so that the loads of four rows of B are in flight
+  // together.
+  for (int p0 = as; p0 < ae; p0 += 64) {
+    const int mine = p0 + lane;
+    int bs_l = 0, be_l = 0;
+    float av_l = 0.f;
+    if (mine < ae) {
+      const int k = a_indices[mine];
+      av_l = a_data[mine];
+      bs_l = wave == 0 ? b_indptr[k] : b_split[3 * k + wave - 1];
+      be_l = wave == 3 ? b_indptr[k + 1] : b_split[3 * k + wave];
     }
+    const int cnt = (ae - p0 < 64) ? (ae - p0) : 64;
+    for (int e = 0; e < cnt; e += 4) {
+      int bs[4], be[4], col[4];
+      float av[4], bv[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int src = (e + u < cnt) ? e + u : e;
+        bs[u] = __builtin_amdgcn_readlane(bs_l, src);
+        be[u] = (e + u < cnt) ? __builtin_amdgcn_readlane(be_l, src) : bs[u];
+        av[u] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, av_l), src));
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int q = bs[u] + lane;
+        col[u] = (q < be[u]) ? b_indices[q] : -1;
+        bv[u] = (q < be[u]) ? b_data[q] : 0.f;
+      }
+      // in the order of A's entries; the lanes of one step hold distinct columns of one row of B
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        if (col[u] >= 0) {
+          if (MODE == 0) lds[col[u]] += av[u] * bv[u];
+          else if (MODE == 1) cacc[slot_lo + lower_bound_i32(cidx + slot_lo, slot_n, col[u])] += av[u] * bv[u];
+          else atomicAdd(&c_data[cs + slot_lo + lower_bound_i32(c_indices + cs + slot_lo, slot_n, col[u])], av[u] * bv[u]);
+        }
+        for (int q0 = bs[u] + 64 + lane; q0 < be[u]; q0 += 64) {   // a share longer than one wave
+          const int c = b_indices[q0];
+          const float t = av[u] * b_data[q0];
+          if (MODE == 0) lds[c] += t;
+          else if (MODE == 1) cacc[slot_lo + lower_bound_i32(cidx + slot_lo, slot_n, c)] += t;
+          else atomicAdd(&c_data[cs + slot_lo + lower_bound_i32(c_indices + cs + slot_lo, slot_n, c)], t);
+        }
+      }
+    }
+  }
+  if (MODE == 2) return;
+  __syncthreads();
+  if (MODE == 0) {
+    for (int p = threadIdx.x; p < n; p += blockDim.x) c_data[cs + p] = lds[c_indices[cs + p]];
+  } else {
+    for (int p = threadIdx.x; p < n; p += blockDim.x) c_data[cs + p] = cacc[p];
   }
 }
 
@@ -345,14 +461,54 @@ bppsa_status bppsa_launch_spgemm_indices(const bppsa_csr& A, const bppsa_csr& B,
   return BPPSA_OK;
 }
 
-bppsa_status bppsa_launch_spgemm_numeric(const bppsa_csr& A, const bppsa_csr& B, const int32_t* c_indptr,
-                                         const int32_t* c_indices, float* c_data, hipStream_t stream) {
-  if (B.cols <= kNumericCap)
-    spgemm_numeric_kernel<true><<<A.rows, 256, 0, stream>>>(B.cols, A.indptr, A.indices, A.data, B.indptr, B.indices,
-                                                            B.data, c_indptr, c_indices, c_data);
-  else
-    spgemm_numeric_kernel<false><<<A.rows, 256, 0, stream>>>(B.cols, A.indptr, A.indices, A.data, B.indptr,
-                                                             B.indices, B.data, c_indptr, c_indices, c_data);
+bppsa_status bppsa_launch_row_splits(const bppsa_csr& B, int32_t* split, hipStream_t stream) {
+  if (B.rows < 1) return BPPSA_OK;
+  row_splits_kernel<<<bppsa_ceil_div(3 * B.rows, 256), 256, 0, stream>>>(B.rows, B.cols, B.indptr, B.indices, split);
+  BPPSA_CHECK_LAUNCH();
+  return BPPSA_OK;
+}
+
+int bppsa_spgemm_numeric_kind(int64_t madds, int64_t c_nnz, int c_max_row, int b_cols) {
+  if (madds == c_nnz) return BPPSA_SPGEMM_SINGLE;
+  if (c_max_row <= kWaveRowCap) return BPPSA_SPGEMM_WAVE;
+  if (b_cols <= kBlockDenseCols) return BPPSA_SPGEMM_BLOCK_DENSE;
+  if (c_max_row <= kBlockStagedCap) return BPPSA_SPGEMM_BLOCK_STAGED;
+  return BPPSA_SPGEMM_BLOCK_GLOBAL;
+}
+
+bppsa_status bppsa_launch_spgemm_numeric(int kind, const bppsa_csr& A, const bppsa_csr& B, const int32_t* b_split,
+                                         const int32_t* c_indptr, const int32_t* c_indices, float* c_data,
+                                         hipStream_t stream) {
+  if (A.rows < 1) return BPPSA_OK;
+#define BPPSA_NUMERIC_ARGS A.indptr, A.indices, A.data, B.indptr, B.indices, B.data
+  switch (kind) {
+    case BPPSA_SPGEMM_SINGLE:
+      spgemm_numeric_single_kernel<<<bppsa_ceil_div(A.rows, 4), 256, 0, stream>>>(A.rows, BPPSA_NUMERIC_ARGS, c_indptr,
+                                                                                  c_indices, c_data);
+      break;
+    case BPPSA_SPGEMM_WAVE:
+      spgemm_numeric_wave_kernel<<<bppsa_ceil_div(A.rows, 4), 256, 0, stream>>>(A.rows, BPPSA_NUMERIC_ARGS, c_indptr,
+                                                                                c_indices, c_data);
+      break;
+    case BPPSA_SPGEMM_BLOCK_DENSE:
+      if (!b_split) return BPPSA_EINVAL;
+      spgemm_numeric_block_kernel<0><<<A.rows, 256, 0, stream>>>(B.cols, BPPSA_NUMERIC_ARGS, b_split, c_indptr,
+                                                                 c_indices, c_data);
+      break;
+    case BPPSA_SPGEMM_BLOCK_STAGED:
+      if (!b_split) return BPPSA_EINVAL;
+      spgemm_numeric_block_kernel<1><<<A.rows, 256, 0, stream>>>(B.cols, BPPSA_NUMERIC_ARGS, b_split, c_indptr,
+                                                                 c_indices, c_data);
+      break;
+    case BPPSA_SPGEMM_BLOCK_GLOBAL:
+      if (!b_split) return BPPSA_EINVAL;
+      spgemm_numeric_block_kernel<2><<<A.rows, 256, 0, stream>>>(B.cols, BPPSA_NUMERIC_ARGS, b_split, c_indptr,
+                                                                 c_indices, c_data);
+      break;
+    default:
+      return BPPSA_EINVAL;
+  }
+#undef BPPSA_NUMERIC_ARGS
   BPPSA_CHECK_LAUNCH();
   return BPPSA_OK;
 }

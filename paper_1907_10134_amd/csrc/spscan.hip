@@ -31,6 +31,9 @@ struct Product {          // C = left * right; ids < n are inputs, ids >= n are 
   int32_t* indices;
   float* data;
   bool live;
+  int numeric_kind;       // which numeric kernel forms the values (chosen when the plan is built)
+  int32_t* right_split;   // BLOCK kinds: where each row of the right operand crosses the column quarters
+  int max_row;            // longest row of the product
 };
 
 struct Vec {              // id 0 is the caller's seed
@@ -271,6 +274,23 @@ extern "C" bppsa_status bppsa_spscan_plan_create(int n, const bppsa_csr* Jt, int
     if (!pr.indices || !pr.data) { st = BPPSA_EWORKSPACE; break; }
     st = bppsa_launch_spgemm_indices(L, R, pr.indptr, pr.indices, s);
     if (st != BPPSA_OK) break;
+    // the numeric kernel depends on the longest row of the product (read back once, here)
+    {
+      std::vector<int32_t> hp((size_t)pr.rows + 1);
+      if (hipMemcpyAsync(hp.data(), pr.indptr, hp.size() * sizeof(int32_t), hipMemcpyDeviceToHost, s) != hipSuccess ||
+          hipStreamSynchronize(s) != hipSuccess) { st = BPPSA_EHIP; break; }
+      int mx = 0;
+      for (int r = 0; r < pr.rows; ++r) mx = hp[r + 1] - hp[r] > mx ? hp[r + 1] - hp[r] : mx;
+      pr.max_row = mx;
+    }
+    pr.numeric_kind = bppsa_spgemm_numeric_kind(pr.madds, pr.nnz, pr.max_row, R.cols);
+    pr.right_split = nullptr;
+    if (pr.numeric_kind >= BPPSA_SPGEMM_BLOCK_DENSE) {
+      pr.right_split = static_cast<int32_t*>(ar.take((size_t)3 * R.rows * sizeof(int32_t)));
+      if (!pr.right_split) { st = BPPSA_EWORKSPACE; break; }
+      st = bppsa_launch_row_splits(R, pr.right_split, s);
+      if (st != BPPSA_OK) break;
+    }
     P.mm_flops += 2 * pr.madds;
     P.live_product_ids.push_back((int)i);
   }
@@ -362,8 +382,8 @@ extern "C" bppsa_status bppsa_spscan_run(const bppsa_spscan_plan* plan, const bp
     bppsa_status st;
     if (op.kind == kSpgemm) {
       const Product& pr = P.prods[op.mat - P.n];
-      st = bppsa_launch_spgemm_numeric(mat_desc(P, Jt, pr.left), mat_desc(P, Jt, pr.right),
-                                       pr.indptr, pr.indices, pr.data, s);
+      st = bppsa_launch_spgemm_numeric(pr.numeric_kind, mat_desc(P, Jt, pr.left), mat_desc(P, Jt, pr.right),
+                                       pr.right_split, pr.indptr, pr.indices, pr.data, s);
     } else {
       if (op.tail && !grads[P.n - 1]) continue;     // inclusive tail not requested
       // a diagonal matrix that consumes this product is applied in the same launch

@@ -193,3 +193,100 @@ def test_spscan_config4_full_network(bp, up_levels):
     if up_levels:
         assert _check_products(bp, plan, jts_ref) > 0
     plan.close()
+
+
+def _csr_to_gpu(bp, m):
+    m = sp.csr_matrix(m)
+    m.sort_indices()
+    return bp.CsrMatrix(m.shape[0], m.shape[1], to_gpu(m.indptr.astype(np.int32)), to_gpu(m.indices.astype(np.int32)),
+                        to_gpu(m.data.astype(np.float32)))
+
+
+def _chain_with_one_product(bp, left, right, rng):
+    """A five-matrix chain in scan order whose level-0 up-sweep forms exactly left * right as a live
+    product: [D0, right, left, D3, D4] with small dense end pieces."""
+    d0 = sp.csr_matrix(rng.standard_normal((right.shape[1], 3)).astype(np.float32))
+    d3 = sp.csr_matrix(rng.standard_normal((5, left.shape[0])).astype(np.float32))
+    d4 = sp.csr_matrix(rng.standard_normal((4, 5)).astype(np.float32))
+    return [d0, sp.csr_matrix(right), sp.csr_matrix(left), d3, d4]
+
+
+@pytest.mark.parametrize("case", ["wave", "block_dense", "block_staged", "block_global"])
+def test_spgemm_numeric_kinds_match_oracle_and_repeat_bit_identically(bp, case):
+    """The numeric phase of the CSR x CSR product, one case per kernel that sums terms: values against
+    the oracle's product, and the same bits on every run (each value is formed by one wave in a fixed
+    order).  block_global is a product whose rows have more than 6144 entries over more than 12288
+    columns, which is what sends a row to accumulators in global memory."""
+    import torch
+    rng = np.random.default_rng(len(case))
+    if case == "wave":                      # short rows with real sums
+        left = sp.random(300, 200, density=0.1, random_state=1, format="csr", dtype=np.float32)
+        right = sp.random(200, 500, density=0.05, random_state=2, format="csr", dtype=np.float32)
+    elif case == "block_dense":             # rows longer than 1024 entries, at most 12288 columns
+        left = sp.random(40, 300, density=0.3, random_state=3, format="csr", dtype=np.float32)
+        right = sp.random(300, 9000, density=0.02, random_state=4, format="csr", dtype=np.float32)
+    elif case == "block_staged":            # more than 12288 columns, rows of 1025..6144 entries
+        left = sp.random(30, 200, density=0.2, random_state=5, format="csr", dtype=np.float32)
+        right = sp.random(200, 20000, density=0.005, random_state=6, format="csr", dtype=np.float32)
+    else:                                   # more than 12288 columns and rows longer than 6144 entries
+        left = sp.random(6, 120, density=0.9, random_state=7, format="csr", dtype=np.float32)
+        right = sp.random(120, 16384, density=0.03, random_state=8, format="csr", dtype=np.float32)
+    left.sort_indices()
+    right.sort_indices()
+    ref = ocnn.csr_product(left, right)
+    longest = int(np.max(np.diff(ref.indptr)))
+    if case == "wave":
+        assert longest <= 1024 and ref.nnz < left.nnz * right.nnz
+    elif case == "block_dense":
+        assert longest > 1024 and right.shape[1] <= 12288
+    elif case == "block_staged":
+        assert 1024 < longest <= 6144 and right.shape[1] > 12288
+    else:
+        assert longest > 6144 and right.shape[1] > 12288
+    chain = _chain_with_one_product(bp, left, right, rng)
+    jts = [_csr_to_gpu(bp, m) for m in chain]
+    seed = to_gpu(rng.standard_normal(chain[0].shape[1]).astype(np.float32))
+    arena = torch.empty((1 << 28,), dtype=torch.uint8, device="cuda")
+    plan = bp.SpscanPlan(jts, 1, arena)
+    grads = [torch.empty((m.rows,), dtype=torch.float32, device="cuda") for m in jts]
+    found = None
+    runs = []
+    for _ in range(3):
+        plan.run(jts, seed, grads)
+        torch.cuda.synchronize()
+        for k in range(plan.num_products()):
+            got, l, r = plan.product(k)
+            if (l, r) == (2, 1):
+                found = got
+                runs.append(to_np(got.data).copy())
+    assert found is not None, "the chain did not produce left * right"
+    _assert_same_csr(found, ref, values=False)
+    assert rel_err(runs[0], ref.data) <= 1e-5
+    assert all(np.array_equal(runs[0], r) for r in runs[1:])
+    # and the gradients of the whole chain against the oracle's serial sparse scan
+    g_ref = ocnn.sparse_linear_scan([sp.csr_matrix(m, dtype=np.float64) for m in chain], to_np(seed).astype(np.float64))
+    for k in range(len(chain)):
+        assert rel_err(to_np(grads[k]), g_ref[k]) <= TOL
+    plan.close()
+
+
+def test_spscan_config4_products_repeat_bit_identically(bp):
+    """configs[4] with two up-sweep levels: the values of every CSR x CSR product are the same bits
+    on two runs."""
+    import torch
+    layers, image, label = workloads.cnn_layers()
+    acts32, aux = _rounded_forward(layers, image)
+    jts = _gpu_jacobians(bp, layers, acts32)
+    seed = to_gpu(np.random.default_rng(0).standard_normal(jts[0].cols).astype(np.float32))
+    arena = torch.empty((1 << 30,), dtype=torch.uint8, device="cuda")
+    plan = bp.SpscanPlan(jts, 2, arena)
+    grads = [torch.empty((m.rows,), dtype=torch.float32, device="cuda") for m in jts]
+    snaps = []
+    for _ in range(2):
+        plan.run(jts, seed, grads)
+        torch.cuda.synchronize()
+        snaps.append([plan.product(k)[0].data.clone() for k in range(plan.num_products())] + [g.clone() for g in grads])
+        for k in range(plan.num_products()):
+            plan.product(k)[0].data.zero_()
+    assert all(torch.equal(a, b) for a, b in zip(*snaps))
+    plan.close()
