@@ -25,19 +25,20 @@ bppsa_status bppsa_launch_spgemm_indices(const bppsa_csr& A, const bppsa_csr& B,
                                          int32_t* c_indices, hipStream_t stream);
 // Values of C for a known structure (c_indptr, c_indices); c_data is overwritten.  `kind` says
 // which kernel forms them and is chosen once per product from the number of multiply-adds, nnz(C),
-// the longest row of C and the number of columns of B; the BLOCK kinds also need the table
-// b_split [3 * rows(B)] that bppsa_launch_row_splits writes for B.
+// the longest row of C (c_max_row, which the launch takes again to size LDS) and the number of
+// columns of B; the BLOCK kinds also need the table b_split [3 * rows(B)] that
+// bppsa_launch_row_splits writes for B.
 enum {
   BPPSA_SPGEMM_SINGLE = 0,        // no value of C is a sum: nothing to order
   BPPSA_SPGEMM_WAVE = 1,          // one wave per row, the row staged in LDS
   BPPSA_SPGEMM_BLOCK_DENSE = 2,   // one workgroup per row, one LDS accumulator per column of B
-  BPPSA_SPGEMM_BLOCK_STAGED = 3,  // one workgroup per row, the row staged in LDS
+  BPPSA_SPGEMM_BLOCK_STAGED = 3,  // one workgroup per row, one LDS accumulator per entry of the row
   BPPSA_SPGEMM_BLOCK_GLOBAL = 4   // one workgroup per row, accumulated in global memory
 };
 int bppsa_spgemm_numeric_kind(int64_t madds, int64_t c_nnz, int c_max_row, int b_cols);
 bppsa_status bppsa_launch_row_splits(const bppsa_csr& B, int32_t* split, hipStream_t stream);
 bppsa_status bppsa_launch_spgemm_numeric(int kind, const bppsa_csr& A, const bppsa_csr& B, const int32_t* b_split,
                                          const int32_t* c_indptr, const int32_t* c_indices, float* c_data,
-                                         hipStream_t stream);
+                                         int c_max_row, hipStream_t stream);
 
 constexpr int kBppsaMaxSpgemmCols = 1 << 20;  // LDS bitmap: one bit per column of B

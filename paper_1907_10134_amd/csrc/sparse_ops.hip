@@ -163,10 +163,9 @@ spgemm_symbolic_kernel(int words, const int32_t* __restrict__ a_indptr,
 }
 
 // ---- numeric phase of C = A B for a known structure ---------------------------------------------
-// Every value of C is formed by ONE wave, which adds the terms of an entry in a fixed order
-// (entries of A's row in storage order), so the values are the same bits on every run; no two
-// waves ever add to the same accumulator.  Three kernels, chosen once per product when the plan
-// is built:
+// Every value of C is formed by ONE wave, which adds the terms of an entry in an order fixed by
+// the structure of A and B alone, so the values are the same bits on every run; no two waves ever
+// add to the same accumulator.  Three kernels, chosen once per product when the plan is built:
 //
 //   single : every entry of C is exactly one product a * b (the number of multiply-adds equals
 //            nnz(C): a diagonal or selection matrix on either side, i.e. every product with a ReLU
@@ -177,11 +176,11 @@ spgemm_symbolic_kernel(int words, const int32_t* __restrict__ a_indptr,
 //   block  : longer rows: one workgroup per row.  The columns are cut into four equal ranges, one
 //            per wave, and a table built with the plan says where each row of B crosses those
 //            boundaries, so a wave reads exactly its share of every row of B and owns its share of
-//            the accumulators: one per column when B has at most kBlockDenseCols columns, else
-//            the row's entries staged in LDS (up to kBlockStagedCap) or left in global memory.
+//            the accumulators: one per column of B, or one per entry of the longest row of C
+//            plus a rank table (whichever takes less LDS), or, when neither fits kBlockLdsBytes,
+//            the row itself in global memory.
 constexpr int kWaveRowCap = 1024;
-constexpr int kBlockDenseCols = 12288;
-constexpr int kBlockStagedCap = 6144;
+constexpr size_t kBlockLdsBytes = 64 * 1024;   // most LDS one workgroup of the BLOCK kinds takes
 
 // first position in sorted idx[0..n) whose value is >= col
 __device__ __forceinline__ int lower_bound_i32(const int32_t* idx, int n, int col) {
@@ -304,10 +303,52 @@ spgemm_numeric_wave_kernel(int rows, const int32_t* __restrict__ a_indptr, const
   for (int j = lane; j < n; j += 64) c_data[cs + j] = acc[j];
 }
 
-// MODE 0: one accumulator per column of B (LDS);  MODE 1: the row's entries staged in LDS, slots by
-// binary search;  MODE 2: the same search on the row in global memory, where the additions are
-// memory-side add operations: all additions to one entry come from one wave, in its program
-// order, so they too are applied in a fixed order.
+// One workgroup of four waves per row of C; wave w owns the columns [w q, (w + 1) q), q = ceil(cols / 4),
+// and with them every value of the row that falls there, so each value is summed by one wave in
+// one order.
+//   MODE 0: one LDS accumulator per column of B.
+//   MODE 1: one LDS accumulator per entry of the row; the place of a column is its rank among the
+//           row's columns, read from a table of (bits, entries before) per 32 columns.
+//   MODE 2: the row stays in global memory, places by binary search; the additions are memory-side
+//           add operations, all additions to one entry issued by one wave in program order.
+// The wave walks A's row 64 entries at a time (one per lane: value and the bounds of its share of
+// the row of B), and takes their shares in pieces of 64 entries: first pieces of all entries, then
+// second pieces, and so on.  Pieces are fetched kDepth at a time and the fetch of the next kDepth
+// is issued before the current ones are added, so the additions run under the memory latency.
+constexpr int kDepth = 8;
+
+struct Pieces {
+  int col[kDepth];
+  float bv[kDepth];
+  float av[kDepth];
+};
+
+// takes up to kDepth entries out of `todo` (one bit per lane whose share has a piece number `round`)
+__device__ __forceinline__ int fetch_pieces(Pieces& pc, unsigned long long& todo, int round, int lane, int bs_l,
+                                            int be_l, float av_l, const int32_t* __restrict__ b_indices,
+                                            const float* __restrict__ b_data) {
+  int got = 0;
+#pragma unroll
+  for (int u = 0; u < kDepth; ++u) {
+    pc.col[u] = -1;
+    pc.bv[u] = 0.f;
+    pc.av[u] = 0.f;
+    if (todo != 0) {                                   // uniform over the wave
+      const int src = __builtin_ctzll(todo);
+      todo &= todo - 1;
+      const int q = __builtin_amdgcn_readlane(bs_l, src) + 64 * round + lane;
+      const int e = __builtin_amdgcn_readlane(be_l, src);
+      pc.av[u] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, av_l), src));
+      if (q < e) {
+        pc.col[u] = b_indices[q];
+        pc.bv[u] = b_data[q];
+      }
+      ++got;
+    }
+  }
+  return got;
+}
+
 template <int MODE>
 __global__ void __launch_bounds__(256)
 spgemm_numeric_block_kernel(int b_cols, const int32_t* __restrict__ a_indptr, const int32_t* __restrict__ a_indices,
@@ -315,40 +356,55 @@ spgemm_numeric_block_kernel(int b_cols, const int32_t* __restrict__ a_indptr, co
                             const int32_t* __restrict__ b_indices, const float* __restrict__ b_data,
                             const int32_t* __restrict__ b_split, const int32_t* __restrict__ c_indptr,
                             const int32_t* __restrict__ c_indices, float* __restrict__ c_data) {
-  __shared__ float lds[kBlockDenseCols];
+  extern __shared__ float lds[];
   const int row = blockIdx.x;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int cs = c_indptr[row], ce = c_indptr[row + 1];
   const int n = ce - cs;
   const int as = a_indptr[row], ae = a_indptr[row + 1];
   if (n == 0) return;                            // uniform over the workgroup
-  float* cacc = lds;
-  int32_t* cidx = reinterpret_cast<int32_t*>(lds + kBlockDenseCols / 2);
+  // MODE 1: rank table first (8 bytes per 32 columns), then the accumulators
+  const int words = (b_cols + 31) >> 5;
+  uint2* rk = reinterpret_cast<uint2*>(lds);
+  float* cacc = lds + 2 * words;
   if (MODE == 0) {
     for (int p = threadIdx.x; p < n; p += blockDim.x) lds[c_indices[cs + p]] = 0.f;
   } else if (MODE == 1) {
+    for (int w = threadIdx.x; w < words; w += blockDim.x) rk[w] = make_uint2(0u, 0u);
+    __syncthreads();
     for (int p = threadIdx.x; p < n; p += blockDim.x) {
-      cidx[p] = c_indices[cs + p];
+      const int c = c_indices[cs + p];
+      atomicOr(&rk[c >> 5].x, 1u << (c & 31));   // integer: the result does not depend on the order
+      if (p == 0 || (c_indices[cs + p - 1] >> 5) != (c >> 5)) rk[c >> 5].y = (unsigned)p;
       cacc[p] = 0.f;
     }
   } else {
     for (int p = cs + threadIdx.x; p < ce; p += blockDim.x) c_data[p] = 0.f;
   }
   __syncthreads();
-  // the slots of this wave's column range (MODE 1 and 2): [slot_lo, slot_hi)
   const int quarter = (b_cols + 3) / 4;
-  int slot_lo = 0, slot_n = n;
-  if (MODE == 1) {
-    slot_lo = lower_bound_i32(cidx, n, wave * quarter);
-    slot_n = lower_bound_i32(cidx, n, (wave + 1) * quarter) - slot_lo;
-  } else if (MODE == 2) {
+  int slot_lo = 0, slot_n = n;                   // MODE 2: the places of this wave's columns
+  if (MODE == 2) {
     slot_lo = lower_bound_i32(c_indices + cs, n, wave * quarter);
     slot_n = lower_bound_i32(c_indices + cs, n, (wave + 1) * quarter) - slot_lo;
   }
-  // Every wave walks all of A's row in storage order but reads only its share of each row of B.
-  // Each lane first fetches one entry of A's row and the bounds of that share; the wave then
-  // takes those entries four at a time so that the loads of four rows of B are in flight
-  // together.
+  auto add = [&](const Pieces& pc) {
+#pragma unroll
+    for (int u = 0; u < kDepth; ++u) {
+      const int c = pc.col[u];
+      if (c >= 0) {                              // the lanes of one piece hold distinct columns
+        const float t = pc.av[u] * pc.bv[u];
+        if (MODE == 0) {
+          lds[c] += t;
+        } else if (MODE == 1) {
+          const uint2 r = rk[c >> 5];
+          cacc[r.y + __builtin_popcount(r.x & ((1u << (c & 31)) - 1u))] += t;
+        } else {
+          atomicAdd(&c_data[cs + slot_lo + lower_bound_i32(c_indices + cs + slot_lo, slot_n, c)], t);
+        }
+      }
+    }
+  };
   for (int p0 = as; p0 < ae; p0 += 64) {
     const int mine = p0 + lane;
     int bs_l = 0, be_l = 0;
@@ -359,38 +415,15 @@ spgemm_numeric_block_kernel(int b_cols, const int32_t* __restrict__ a_indptr, co
       bs_l = wave == 0 ? b_indptr[k] : b_split[3 * k + wave - 1];
       be_l = wave == 3 ? b_indptr[k + 1] : b_split[3 * k + wave];
     }
-    const int cnt = (ae - p0 < 64) ? (ae - p0) : 64;
-    for (int e = 0; e < cnt; e += 4) {
-      int bs[4], be[4], col[4];
-      float av[4], bv[4];
-#pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const int src = (e + u < cnt) ? e + u : e;
-        bs[u] = __builtin_amdgcn_readlane(bs_l, src);
-        be[u] = (e + u < cnt) ? __builtin_amdgcn_readlane(be_l, src) : bs[u];
-        av[u] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, av_l), src));
-      }
-#pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const int q = bs[u] + lane;
-        col[u] = (q < be[u]) ? b_indices[q] : -1;
-        bv[u] = (q < be[u]) ? b_data[q] : 0.f;
-      }
-      // in the order of A's entries; the lanes of one step hold distinct columns of one row of B
-#pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        if (col[u] >= 0) {
-          if (MODE == 0) lds[col[u]] += av[u] * bv[u];
-          else if (MODE == 1) cacc[slot_lo + lower_bound_i32(cidx + slot_lo, slot_n, col[u])] += av[u] * bv[u];
-          else atomicAdd(&c_data[cs + slot_lo + lower_bound_i32(c_indices + cs + slot_lo, slot_n, col[u])], av[u] * bv[u]);
-        }
-        for (int q0 = bs[u] + 64 + lane; q0 < be[u]; q0 += 64) {   // a share longer than one wave
-          const int c = b_indices[q0];
-          const float t = av[u] * b_data[q0];
-          if (MODE == 0) lds[c] += t;
-          else if (MODE == 1) cacc[slot_lo + lower_bound_i32(cidx + slot_lo, slot_n, c)] += t;
-          else atomicAdd(&c_data[cs + slot_lo + lower_bound_i32(c_indices + cs + slot_lo, slot_n, c)], t);
-        }
+    for (int round = 0;; ++round) {
+      unsigned long long todo = __ballot(be_l - bs_l > 64 * round);
+      if (todo == 0) break;
+      Pieces cur, nxt;
+      int have = fetch_pieces(cur, todo, round, lane, bs_l, be_l, av_l, b_indices, b_data);
+      while (have > 0) {
+        have = fetch_pieces(nxt, todo, round, lane, bs_l, be_l, av_l, b_indices, b_data);
+        add(cur);
+        cur = nxt;
       }
     }
   }
@@ -468,17 +501,25 @@ bppsa_status bppsa_launch_row_splits(const bppsa_csr& B, int32_t* split, hipStre
   return BPPSA_OK;
 }
 
+static size_t dense_lds_bytes(int b_cols) { return (size_t)b_cols * sizeof(float); }
+static size_t ranked_lds_bytes(int c_max_row, int b_cols) {
+  return (size_t)c_max_row * sizeof(float) + (size_t)((b_cols + 31) / 32) * 8;
+}
+
 int bppsa_spgemm_numeric_kind(int64_t madds, int64_t c_nnz, int c_max_row, int b_cols) {
   if (madds == c_nnz) return BPPSA_SPGEMM_SINGLE;
   if (c_max_row <= kWaveRowCap) return BPPSA_SPGEMM_WAVE;
-  if (b_cols <= kBlockDenseCols) return BPPSA_SPGEMM_BLOCK_DENSE;
-  if (c_max_row <= kBlockStagedCap) return BPPSA_SPGEMM_BLOCK_STAGED;
+  const size_t dense = dense_lds_bytes(b_cols), ranked = ranked_lds_bytes(c_max_row, b_cols);
+  // one accumulator per column costs one LDS access less per term: it wins unless the rank table
+  // and the row's accumulators are clearly smaller (more workgroups per compute unit)
+  if (dense <= kBlockLdsBytes && (dense <= 16 * 1024 || 4 * dense <= 5 * ranked)) return BPPSA_SPGEMM_BLOCK_DENSE;
+  if (ranked <= kBlockLdsBytes) return BPPSA_SPGEMM_BLOCK_STAGED;
   return BPPSA_SPGEMM_BLOCK_GLOBAL;
 }
 
 bppsa_status bppsa_launch_spgemm_numeric(int kind, const bppsa_csr& A, const bppsa_csr& B, const int32_t* b_split,
                                          const int32_t* c_indptr, const int32_t* c_indices, float* c_data,
-                                         hipStream_t stream) {
+                                         int c_max_row, hipStream_t stream) {
   if (A.rows < 1) return BPPSA_OK;
 #define BPPSA_NUMERIC_ARGS A.indptr, A.indices, A.data, B.indptr, B.indices, B.data
   switch (kind) {
@@ -492,12 +533,20 @@ bppsa_status bppsa_launch_spgemm_numeric(int kind, const bppsa_csr& A, const bpp
       break;
     case BPPSA_SPGEMM_BLOCK_DENSE:
       if (!b_split) return BPPSA_EINVAL;
-      spgemm_numeric_block_kernel<0><<<A.rows, 256, 0, stream>>>(B.cols, BPPSA_NUMERIC_ARGS, b_split, c_indptr,
+      if (dense_lds_bytes(B.cols) > kBlockLdsBytes) return BPPSA_EINVAL;
+      if (dense_lds_bytes(B.cols) > 48 * 1024)
+        BPPSA_HIP_TRY(hipFuncSetAttribute((const void*)spgemm_numeric_block_kernel<0>,
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)kBlockLdsBytes));
+      spgemm_numeric_block_kernel<0><<<A.rows, 256, dense_lds_bytes(B.cols), stream>>>(B.cols, BPPSA_NUMERIC_ARGS, b_split, c_indptr,
                                                                  c_indices, c_data);
       break;
     case BPPSA_SPGEMM_BLOCK_STAGED:
       if (!b_split) return BPPSA_EINVAL;
-      spgemm_numeric_block_kernel<1><<<A.rows, 256, 0, stream>>>(B.cols, BPPSA_NUMERIC_ARGS, b_split, c_indptr,
+      if (ranked_lds_bytes(c_max_row, B.cols) > kBlockLdsBytes) return BPPSA_EINVAL;
+      if (ranked_lds_bytes(c_max_row, B.cols) > 48 * 1024)
+        BPPSA_HIP_TRY(hipFuncSetAttribute((const void*)spgemm_numeric_block_kernel<1>,
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)kBlockLdsBytes));
+      spgemm_numeric_block_kernel<1><<<A.rows, 256, ranked_lds_bytes(c_max_row, B.cols), stream>>>(B.cols, BPPSA_NUMERIC_ARGS, b_split, c_indptr,
                                                                  c_indices, c_data);
       break;
     case BPPSA_SPGEMM_BLOCK_GLOBAL:

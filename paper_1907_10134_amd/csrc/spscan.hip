@@ -383,7 +383,7 @@ extern "C" bppsa_status bppsa_spscan_run(const bppsa_spscan_plan* plan, const bp
     if (op.kind == kSpgemm) {
       const Product& pr = P.prods[op.mat - P.n];
       st = bppsa_launch_spgemm_numeric(pr.numeric_kind, mat_desc(P, Jt, pr.left), mat_desc(P, Jt, pr.right),
-                                       pr.right_split, pr.indptr, pr.indices, pr.data, s);
+                                       pr.right_split, pr.indptr, pr.indices, pr.data, pr.max_row, s);
     } else {
       if (op.tail && !grads[P.n - 1]) continue;     // inclusive tail not requested
       // a diagonal matrix that consumes this product is applied in the same launch

@@ -215,34 +215,37 @@ def _chain_with_one_product(bp, left, right, rng):
 def test_spgemm_numeric_kinds_match_oracle_and_repeat_bit_identically(bp, case):
     """The numeric phase of the CSR x CSR product, one case per kernel that sums terms: values against
     the oracle's product, and the same bits on every run (each value is formed by one wave in a fixed
-    order).  block_global is a product whose rows have more than 6144 entries over more than 12288
-    columns, which is what sends a row to accumulators in global memory."""
+    order).  A workgroup takes at most 64 KiB of LDS: 4 bytes per column of the right operand, or 4
+    bytes per entry of the longest row plus 8 bytes per 32 columns; block_global is a product that
+    fits neither, which is what sends a row to accumulators in global memory."""
     import torch
     rng = np.random.default_rng(len(case))
     if case == "wave":                      # short rows with real sums
         left = sp.random(300, 200, density=0.1, random_state=1, format="csr", dtype=np.float32)
         right = sp.random(200, 500, density=0.05, random_state=2, format="csr", dtype=np.float32)
-    elif case == "block_dense":             # rows longer than 1024 entries, at most 12288 columns
+    elif case == "block_dense":             # rows longer than 1024 entries, one accumulator per column fits
         left = sp.random(40, 300, density=0.3, random_state=3, format="csr", dtype=np.float32)
         right = sp.random(300, 9000, density=0.02, random_state=4, format="csr", dtype=np.float32)
-    elif case == "block_staged":            # more than 12288 columns, rows of 1025..6144 entries
+    elif case == "block_staged":            # too many columns for that, but the longest row fits
         left = sp.random(30, 200, density=0.2, random_state=5, format="csr", dtype=np.float32)
         right = sp.random(200, 20000, density=0.005, random_state=6, format="csr", dtype=np.float32)
-    else:                                   # more than 12288 columns and rows longer than 6144 entries
+    else:                                   # neither fits
         left = sp.random(6, 120, density=0.9, random_state=7, format="csr", dtype=np.float32)
-        right = sp.random(120, 16384, density=0.03, random_state=8, format="csr", dtype=np.float32)
+        right = sp.random(120, 20000, density=0.03, random_state=8, format="csr", dtype=np.float32)
     left.sort_indices()
     right.sort_indices()
     ref = ocnn.csr_product(left, right)
     longest = int(np.max(np.diff(ref.indptr)))
+    dense_bytes = 4 * right.shape[1]
+    ranked_bytes = 4 * longest + 8 * ((right.shape[1] + 31) // 32)
     if case == "wave":
         assert longest <= 1024 and ref.nnz < left.nnz * right.nnz
     elif case == "block_dense":
-        assert longest > 1024 and right.shape[1] <= 12288
+        assert longest > 1024 and dense_bytes <= 65536 and 4 * dense_bytes <= 5 * ranked_bytes
     elif case == "block_staged":
-        assert 1024 < longest <= 6144 and right.shape[1] > 12288
+        assert longest > 1024 and dense_bytes > 65536 and ranked_bytes <= 65536
     else:
-        assert longest > 6144 and right.shape[1] > 12288
+        assert longest > 1024 and dense_bytes > 65536 and ranked_bytes > 65536
     chain = _chain_with_one_product(bp, left, right, rng)
     jts = [_csr_to_gpu(bp, m) for m in chain]
     seed = to_gpu(rng.standard_normal(chain[0].shape[1]).astype(np.float32))
