@@ -354,6 +354,24 @@ def cnn_workload(bp, workloads, steps):
         res["up_levels_%d" % U] = {"plan_ms": round(plan_ms, 3), "run_ms": round(run_ms, 4),
                                    "products": plan.num_products(), "mm_flop": mm, "mv_flop": mv,
                                    "arena_bytes": plan.arena_used()}
+        if U:
+            # FLOP per tree level (the series of Section 5.3's static analysis) and the cost of a
+            # plan whose symbolic phase comes from the cache
+            series = {}
+            for st in plan.steps():
+                key = "%s%s_%s" % (st["phase"], "" if st["phase"] in ("linear", "tail") else st["level"], st["kind"])
+                series[key] = series.get(key, 0) + st["flops"]
+            res["up_levels_%d" % U]["flop_by_level"] = series
+            cache = bp.SpscanCache()
+            bp.SpscanPlan(jts, U, arena, cache=cache).close()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            again = bp.SpscanPlan(jts, U, arena, cache=cache)
+            torch.cuda.synchronize()
+            res["up_levels_%d" % U]["plan_cached_ms"] = round((time.perf_counter() - t0) * 1e3, 3)
+            assert cache.stats()[:2] == (1, 1)
+            again.close()
+            cache.close()
         plan.close()
     b = res["csr_bytes"] + 4 * (rows + jts[0].cols)
     res["spmv_chain_gbps"] = round(b / (res["up_levels_0"]["run_ms"] * 1e-3) / 1e9, 2)

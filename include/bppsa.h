@@ -267,7 +267,8 @@ bppsa_status bppsa_spmv(const bppsa_csr* A, const float* x, float* y, void* stre
  *
  * The schedule is Algorithm 1's with only `up_levels` up-sweep levels, a linear
  * scan of the block totals, and the matching down-sweep levels (Section 5.3);
- * up_levels = 0 is the pure matrix-vector chain.  Products that contain the
+ * up_levels = 0 is the pure matrix-vector chain.  Products whose result reaches
+ * no gradient are not planned.  Products that contain the
  * gradient vector are CSR x vector, all others CSR x CSR with the structural
  * pattern (boolean product of the patterns, ascending columns, explicit zeros
  * kept).
@@ -297,6 +298,51 @@ bppsa_status bppsa_spscan_plan_product(const bppsa_spscan_plan* plan, int idx, b
    matrix-vector steps: the static analysis of Section 4.3. */
 bppsa_status bppsa_spscan_plan_flops(const bppsa_spscan_plan* plan, int64_t* mm_flops,
                                      int64_t* mv_flops);
+
+/* The planned steps one by one, in the order bppsa_spscan_run issues them: the per-step view of
+ * the static analysis of Section 4.3, which gives the FLOP-per-step series of Section 5.3.
+ *   kind    BPPSA_STEP_SPMV (CSR x vector) or BPPSA_STEP_SPGEMM (CSR x CSR)
+ *   phase   up-sweep, the serial chain over block totals, down-sweep, or the inclusive tail
+ *   level   up-/down-sweep: tree level d (0 = neighbouring elements); chain: index of the block
+ *   matrix  SPMV: id of the matrix applied; SPGEMM: id of the product formed (ids as in
+ *           bppsa_spscan_plan_product)
+ *   flops   2 per multiply-add: SPMV 2 nnz(matrix); SPGEMM 2 x sum over stored (i, k) of the left
+ *           operand of the stored entries in row k of the right operand
+ *   numeric_kind  SPGEMM: which kernel forms the values (0 nothing to sum, 1 one wave per row,
+ *           2/3/4 one workgroup per row with accumulators per column / per entry / in global
+ *           memory); -1 for SPMV
+ */
+enum { BPPSA_STEP_SPMV = 0, BPPSA_STEP_SPGEMM = 1 };
+enum { BPPSA_PHASE_UP = 0, BPPSA_PHASE_CHAIN = 1, BPPSA_PHASE_DOWN = 2, BPPSA_PHASE_TAIL = 3 };
+typedef struct bppsa_spscan_step {
+  int32_t kind, phase, level, matrix;
+  int64_t flops;
+  int32_t numeric_kind;
+} bppsa_spscan_step;
+int bppsa_spscan_plan_num_steps(const bppsa_spscan_plan* plan);
+bppsa_status bppsa_spscan_plan_step_flops(const bppsa_spscan_plan* plan, int idx, bppsa_spscan_step* out);
+
+/* A cache of symbolic phases (Section 4.3: the structures depend on the architecture alone, so
+ * they are worth keeping across plans).  bppsa_spscan_plan_create_cached behaves like
+ * bppsa_spscan_plan_create, except that the product structures live in device memory the cache
+ * allocates (hipMalloc, on a miss only) and keeps until bppsa_spscan_cache_destroy, and that a call
+ * whose inputs have the fingerprint of an earlier call (n, up_levels, shapes, and a 128-bit hash of
+ * every indptr and indices array, formed on the device) takes the structures from that call and
+ * runs no symbolic kernel.  The arena then holds only product values and vectors.  Equality of
+ * patterns is decided by the fingerprint, not by comparing the arrays.  A cache belongs to the
+ * device that was current at bppsa_spscan_cache_create (BPPSA_EINVAL on another), may be used from
+ * several host threads (calls are serialised), and must outlive the plans made through it.
+ * bppsa_spscan_cache_stats: plans served from the cache, plans that ran the symbolic phase, the
+ * number of products whose structure was computed, and the device bytes held.
+ */
+typedef struct bppsa_spscan_cache bppsa_spscan_cache;
+bppsa_status bppsa_spscan_cache_create(bppsa_spscan_cache** cache);
+void bppsa_spscan_cache_destroy(bppsa_spscan_cache* cache);
+bppsa_status bppsa_spscan_cache_stats(bppsa_spscan_cache* cache, int64_t* hits, int64_t* misses,
+                                      int64_t* symbolic_products, size_t* device_bytes);
+bppsa_status bppsa_spscan_plan_create_cached(bppsa_spscan_cache* cache, int n, const bppsa_csr* Jt,
+                                             int up_levels, void* arena, size_t arena_bytes,
+                                             void* stream, bppsa_spscan_plan** plan);
 
 bppsa_status bppsa_spscan_run(const bppsa_spscan_plan* plan, const bppsa_csr* Jt,
                               const float* seed, float* const* grads, void* stream);

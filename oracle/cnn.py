@@ -286,3 +286,36 @@ def sparse_linear_scan(jts, seed):
         g = sp.csr_matrix(m) @ g
         out.append(g)
     return out
+
+
+def scan_step_flops(jts, up_levels):
+    """Static FLOP analysis of the scan over CSR transposed Jacobians (Sections 4.3 and 5.3).
+
+    Runs the tree scan of `oracle.scan.tree_scan` with `up_levels` up-sweep levels on the patterns
+    of jts (scan order: jts[0] is the last layer's) and a vector in place of the seed, and returns
+    one record per product of two non-identity operands, in the order the recursion meets them:
+    (phase, level, kind, flops) with phase in {"up", "linear", "down"}, kind "mm" or "mv", and flops
+    = 2 per multiply-add: for C = A B every stored entry (i, k) of A meets every stored entry of row
+    k of B; for y = A x every stored entry of A is used once.  The product that would give the
+    gradient of the first layer's input (the inclusive tail) is not part of the scan and not listed.
+    """
+    from . import scan as _scan
+    mats = [sp.csr_matrix(m) for m in jts]
+    steps = []
+
+    def combine(x, y):                          # x <> y = y x
+        if sp.issparse(x):
+            return csr_product(y, x)
+        return np.ones(y.shape[0])              # only the length of a vector matters here
+
+    def on_step(phase, level, x, y):
+        if sp.issparse(x):
+            row_len = np.diff(x.indptr)
+            flops = 2 * int(row_len[y.indices].sum())
+            steps.append((phase, level, "mm", flops))
+        else:
+            steps.append((phase, level, "mv", 2 * int(y.nnz)))
+
+    a = [np.ones(mats[0].shape[1])] + mats
+    _scan.tree_scan(a, up_levels, combine=combine, is_matrix=sp.issparse, on_step=on_step)
+    return steps

@@ -8,10 +8,12 @@ exclusive scan of the array
 post-condition).  The method reaches exactly the result of Eq. 3, so the
 reference result here is `linear_scan`: the serial scan written out.
 
-`blelloch` follows the up-sweep / down-sweep schedule of Algorithm 1 (with the
-reversed operands in the down-sweep and a symbolic identity that is never
-multiplied) purely as a second, independent opinion and to count which
-products are matrix-matrix and which are matrix-vector.
+`tree_scan` does the work of Algorithm 1 (up-sweep totals of a binary tree,
+prefixes handed down with the operands in the down-sweep's order, a symbolic
+identity that is never multiplied), written as a recursion over the tree, and
+with a block size the hybrid schedule of Section 5.3; it serves purely as a
+second, independent opinion and to count which products are matrix-matrix and
+which are matrix-vector.
 
 Index convention used by the library (time-indexed, 0-based storage):
 Jt[t] = (d h_{t+1} / d h_t)^T for t = 0..T-1, g_t = Jt[t] g_{t+1}, g_T = seed,
@@ -20,9 +22,9 @@ a[0] = g_T and a[k] = Jt[T-k].
 
 Pins (tests/test_oracle_scan.py): H = 1 reduces to numpy's cumulative product;
 identity Jacobians return the seed everywhere; diagonal Jacobians reduce to an
-element-wise cumulative product; `blelloch`, `scan_by_definition` and random
-bracketings agree with `linear_scan` for every n up to 130 (`blelloch_truncated`
-for every n and every number of up-sweep levels); the RNN oracle's matrix-free
+element-wise cumulative product; `tree_scan`, `scan_by_definition` and random
+bracketings agree with `linear_scan` for every n up to 130 (`tree_scan` with a
+block size for every n and every number of up-sweep levels); the RNN oracle's matrix-free
 chain equals `linear_scan` on its explicit Jacobians.
 """
 from __future__ import annotations
@@ -88,95 +90,72 @@ def scan_by_definition(a):
     return out
 
 
-def blelloch(a, counts=None):
-    """Modified Blelloch scan with Algorithm 1's level structure, on a copy of `a`.
+def tree_scan(a, up_levels=None, counts=None, combine=None, is_matrix=None, on_step=None):
+    """Exclusive scan of `a` over a balanced binary tree (the work Algorithm 1 does), with the
+    hybrid schedule of Section 5.3 when `up_levels` is given.
 
-    len(a) = n + 1.  `counts`, if given, is a dict that receives the number of
-    matrix-matrix ("mm") and matrix-vector ("mv") products per phase.
+    len(a) = n + 1.  The array is cut into blocks of 2**up_levels elements (one block holding
+    everything when up_levels is None: the full scan).  Inside a block the elements are the leaves
+    of a binary tree split at powers of two; `total` of a node is the <>-product of its leaves (the
+    up-sweep: node of 2**(d+1) leaves = level d) and is formed only when something asks for it.
+    `spread` hands a node's exclusive prefix down (the down-sweep): the left child inherits it, the
+    right child gets prefix <> total(left).  Between blocks the prefix advances serially,
+    prefix <> total(block): with the gradient vector in the first block these are all matrix-vector
+    products.  The total of the last block, and with it anything built on a[n], is never needed.
+
+    counts: dict receiving the number of matrix-matrix ("mm") and matrix-vector ("mv") products per
+    phase ("up", "linear", "down").  combine(x, y) = x <> y (default `op`) and is_matrix(v) (default:
+    a batched dense matrix) let the same recursion run on other element types; on_step(phase,
+    level, x, y) is called before every product of two non-identity operands.
     """
     a = list(a)
     n = len(a) - 1
-    levels = math.ceil(math.log2(n + 1)) if n >= 1 else 0
-    if counts is not None:
-        counts.update({"up_mm": 0, "up_mv": 0, "down_mm": 0, "down_mv": 0})
-
-    def tally(phase, x, y):
-        if counts is None or x is None or y is None:
-            return
-        kind = "mm" if (x.ndim == 3 and y.ndim == 3) else "mv"
-        counts[phase + "_" + kind] += 1
-
-    def pairs(d):
-        step, half = 1 << (d + 1), 1 << d
-        i = 0
-        while i <= n - half:
-            yield i + half - 1, min(i + step - 1, n)
-            i += step
-
-    for d in range(0, levels - 1):                 # up-sweep
-        for l, r in pairs(d):
-            tally("up", a[l], a[r])
-            a[r] = op(a[l], a[r])
-    a[n] = None                                    # symbolic identity
-    for d in range(levels - 1, -1, -1):            # down-sweep, operands reversed
-        for l, r in pairs(d):
-            t = a[l]
-            a[l] = a[r]
-            tally("down", a[r], t)
-            a[r] = op(a[r], t)
-    return a
-
-
-def blelloch_truncated(a, up_levels, counts=None):
-    """The hybrid schedule of Section 5.3 on a copy of `a`.
-
-    Only the first `up_levels` up-sweep levels run; the block totals they leave
-    behind are then combined by a linear scan (matrix-vector products only,
-    because the first block holds the gradient vector), which deposits every
-    block's exclusive prefix where the down-sweep expects it; the down-sweep then
-    runs its last `up_levels` levels.  up_levels = 0 is the pure linear scan.
-    """
-    a = list(a)
-    n = len(a) - 1
-    levels = math.ceil(math.log2(n + 1)) if n >= 1 else 0
-    U = max(0, min(up_levels, levels - 1)) if levels >= 1 else 0
-    if counts is not None:
-        counts.update({"up_mm": 0, "up_mv": 0, "linear_mv": 0, "down_mm": 0, "down_mv": 0})
-
-    def tally(phase, x, y):
-        if counts is None or x is None or y is None:
-            return
-        kind = "mm" if (x.ndim == 3 and y.ndim == 3) else "mv"
-        counts[phase + "_" + kind] += 1
-
-    def pairs(d):
-        step, half = 1 << (d + 1), 1 << d
-        i = 0
-        while i <= n - half:
-            yield i + half - 1, min(i + step - 1, n)
-            i += step
-
-    for d in range(0, U):
-        for l, r in pairs(d):
-            tally("up", a[l], a[r])
-            a[r] = op(a[l], a[r])
+    combine = op if combine is None else combine
+    is_matrix = (lambda v: v.ndim == 3) if is_matrix is None else is_matrix
+    depth = math.ceil(math.log2(n + 1)) if n >= 1 else 0
+    U = depth if up_levels is None else max(0, min(int(up_levels), max(depth - 1, 0)))
     block = 1 << U
-    prefix = None                                  # exclusive prefix of the current block
-    for i in range(0, n + 1, block):
-        r = min(i + block - 1, n)
-        total = a[r]
-        a[r] = prefix
-        if i + block <= n:                         # a later block needs prefix <> total
-            if prefix is not None:
-                tally("linear", prefix, total)
-            prefix = op(prefix, total)
-    for d in range(U - 1, -1, -1):
-        for l, r in pairs(d):
-            t = a[l]
-            a[l] = a[r]
-            tally("down", a[r], t)
-            a[r] = op(a[r], t)
-    return a
+    if counts is not None:
+        counts.update({"up_mm": 0, "up_mv": 0, "linear_mv": 0, "linear_mm": 0, "down_mm": 0, "down_mv": 0})
+    out = [None] * (n + 1)
+    totals = {}
+
+    def product(phase, level, x, y):
+        if x is not None and y is not None:
+            if counts is not None:
+                counts[phase + ("_mm" if is_matrix(x) and is_matrix(y) else "_mv")] += 1
+            if on_step is not None:
+                on_step(phase, level, x, y)
+        return combine(x, y)
+
+    def total(lo, size):
+        if size == 1:
+            return a[lo]
+        half = size // 2
+        if lo + half > n:                            # nothing in the right half
+            return total(lo, half)
+        if (lo, size) not in totals:
+            totals[(lo, size)] = product("up", half.bit_length() - 1, total(lo, half), total(lo + half, half))
+        return totals[(lo, size)]
+
+    def spread(lo, size, prefix):
+        if size == 1:
+            out[lo] = prefix
+            return
+        half = size // 2
+        if lo + half > n:
+            spread(lo, half, prefix)
+            return
+        right_prefix = product("down", half.bit_length() - 1, prefix, total(lo, half))
+        spread(lo, half, prefix)
+        spread(lo + half, half, right_prefix)
+
+    prefix = None                                    # the symbolic identity, never multiplied
+    for j, lo in enumerate(range(0, n + 1, block)):
+        spread(lo, block, prefix)
+        if lo + block <= n:                          # a later block exists
+            prefix = product("linear", j, prefix, total(lo, block))
+    return out
 
 
 def random_bracketing(items, rng):

@@ -84,6 +84,20 @@ def _load(path=_LIB_PATH):
     lib.bppsa_spscan_plan_flops.restype = c_int
     lib.bppsa_spscan_plan_flops.argtypes = [c_void_p, ctypes.POINTER(ctypes.c_int64),
                                             ctypes.POINTER(ctypes.c_int64)]
+    lib.bppsa_spscan_plan_num_steps.restype = c_int
+    lib.bppsa_spscan_plan_num_steps.argtypes = [c_void_p]
+    lib.bppsa_spscan_plan_step_flops.restype = c_int
+    lib.bppsa_spscan_plan_step_flops.argtypes = [c_void_p, c_int, ctypes.POINTER(SpscanStep)]
+    lib.bppsa_spscan_cache_create.restype = c_int
+    lib.bppsa_spscan_cache_create.argtypes = [ctypes.POINTER(c_void_p)]
+    lib.bppsa_spscan_cache_destroy.restype = None
+    lib.bppsa_spscan_cache_destroy.argtypes = [c_void_p]
+    lib.bppsa_spscan_cache_stats.restype = c_int
+    lib.bppsa_spscan_cache_stats.argtypes = [c_void_p, ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int64),
+                                             ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(c_size_t)]
+    lib.bppsa_spscan_plan_create_cached.restype = c_int
+    lib.bppsa_spscan_plan_create_cached.argtypes = [c_void_p, c_int, ctypes.POINTER(CsrDesc), c_int, c_void_p,
+                                                    c_size_t, c_void_p, ctypes.POINTER(c_void_p)]
     lib.bppsa_spscan_run.restype = c_int
     lib.bppsa_spscan_run.argtypes = [c_void_p, ctypes.POINTER(CsrDesc), c_void_p,
                                      ctypes.POINTER(c_void_p), c_void_p]
@@ -99,6 +113,12 @@ class CsrDesc(ctypes.Structure):
     """Mirror of the C struct bppsa_csr (host struct, device array pointers)."""
     _fields_ = [("rows", ctypes.c_int32), ("cols", ctypes.c_int32), ("nnz", ctypes.c_int64),
                 ("indptr", ctypes.c_void_p), ("indices", ctypes.c_void_p), ("data", ctypes.c_void_p)]
+
+
+class SpscanStep(ctypes.Structure):
+    """Mirror of the C struct bppsa_spscan_step."""
+    _fields_ = [("kind", ctypes.c_int32), ("phase", ctypes.c_int32), ("level", ctypes.c_int32),
+                ("matrix", ctypes.c_int32), ("flops", ctypes.c_int64), ("numeric_kind", ctypes.c_int32)]
 
 
 _lib = _load()
@@ -365,17 +385,57 @@ def _grads_array(grads):
     return arr
 
 
-class SpscanPlan:
-    """Host handle of bppsa_spscan_plan_create; device storage lives in `arena` (a uint8 tensor)."""
+class SpscanCache:
+    """Host handle of bppsa_spscan_cache_create: symbolic phases kept across plans."""
 
-    def __init__(self, jts, up_levels, arena, stream=None):
+    def __init__(self):
+        self._h = ctypes.c_void_p()
+        _check(_lib.bppsa_spscan_cache_create(ctypes.byref(self._h)), "bppsa_spscan_cache_create")
+
+    def stats(self):
+        """(plans served from the cache, plans that ran the symbolic phase, products computed, device bytes)."""
+        h, m, p, b = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int64(), ctypes.c_size_t()
+        _check(_lib.bppsa_spscan_cache_stats(self._h, ctypes.byref(h), ctypes.byref(m), ctypes.byref(p),
+                                             ctypes.byref(b)), "bppsa_spscan_cache_stats")
+        return h.value, m.value, p.value, b.value
+
+    def close(self):
+        if self._h:
+            _lib.bppsa_spscan_cache_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    def __del__(self):
+        self.close()
+
+
+class _DeviceArray:
+    """Device memory owned by the library, exposed to torch.as_tensor without a copy."""
+
+    def __init__(self, ptr, count, typestr, owner):
+        self.owner = owner
+        self.__cuda_array_interface__ = {"shape": (count,), "typestr": typestr, "data": (ptr, False),
+                                         "version": 2, "strides": None}
+
+
+class SpscanPlan:
+    """Host handle of bppsa_spscan_plan_create (or, with `cache`, bppsa_spscan_plan_create_cached);
+    device storage lives in `arena` (a uint8 tensor) and, for the product structures of a cached
+    plan, in the cache."""
+
+    def __init__(self, jts, up_levels, arena, stream=None, cache=None):
         self.n = len(jts)
         self.arena = arena
+        self.cache = cache
         self._h = ctypes.c_void_p()
         descs = _desc_array(jts)
-        _check(_lib.bppsa_spscan_plan_create(self.n, descs, int(up_levels), arena.data_ptr(),
-                                             arena.numel(), _stream(stream), ctypes.byref(self._h)),
-               "bppsa_spscan_plan_create")
+        if cache is None:
+            _check(_lib.bppsa_spscan_plan_create(self.n, descs, int(up_levels), arena.data_ptr(),
+                                                 arena.numel(), _stream(stream), ctypes.byref(self._h)),
+                   "bppsa_spscan_plan_create")
+        else:
+            _check(_lib.bppsa_spscan_plan_create_cached(cache._h, self.n, descs, int(up_levels), arena.data_ptr(),
+                                                        arena.numel(), _stream(stream), ctypes.byref(self._h)),
+                   "bppsa_spscan_plan_create_cached")
 
     def close(self):
         if self._h:
@@ -396,9 +456,24 @@ class SpscanPlan:
         _check(_lib.bppsa_spscan_plan_flops(self._h, ctypes.byref(mm), ctypes.byref(mv)), "bppsa_spscan_plan_flops")
         return mm.value, mv.value
 
+    def steps(self):
+        """The planned steps in issue order: dicts with kind, phase, level, matrix, flops, numeric_kind."""
+        out = []
+        for k in range(int(_lib.bppsa_spscan_plan_num_steps(self._h))):
+            st = SpscanStep()
+            _check(_lib.bppsa_spscan_plan_step_flops(self._h, k, ctypes.byref(st)), "bppsa_spscan_plan_step_flops")
+            out.append({"kind": ("mv", "mm")[st.kind], "phase": ("up", "linear", "down", "tail")[st.phase],
+                        "level": st.level, "matrix": st.matrix, "flops": st.flops, "numeric_kind": st.numeric_kind})
+        return out
+
     def _view(self, ptr, count, dtype):
         off = ptr - self.arena.data_ptr()
-        return self.arena[off:off + 4 * count].view(dtype)
+        if 0 <= off and off + 4 * count <= self.arena.numel():
+            return self.arena[off:off + 4 * count].view(dtype)
+        if count == 0:
+            return torch.empty((0,), dtype=dtype, device=self.arena.device)
+        typestr = "<i4" if dtype == torch.int32 else "<f4"
+        return torch.as_tensor(_DeviceArray(ptr, count, typestr, self.cache), device=self.arena.device)
 
     def product(self, idx):
         """(CsrMatrix view into the arena, left operand id, right operand id)."""

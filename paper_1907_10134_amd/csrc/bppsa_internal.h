@@ -15,6 +15,12 @@
     if (hipGetLastError() != hipSuccess) return BPPSA_EHIP;   \
   } while (0)
 
+#define BPPSA_TRY(expr)                                       \
+  do {                                                        \
+    const bppsa_status st__ = (expr);                         \
+    if (st__ != BPPSA_OK) return st__;                        \
+  } while (0)
+
 #define BPPSA_HIP_TRY(expr)                                   \
   do {                                                        \
     if ((expr) != hipSuccess) return BPPSA_EHIP;              \

@@ -41,4 +41,9 @@ bppsa_status bppsa_launch_spgemm_numeric(int kind, const bppsa_csr& A, const bpp
                                          const int32_t* c_indptr, const int32_t* c_indices, float* c_data,
                                          int c_max_row, hipStream_t stream);
 
+// Adds a fingerprint of a[0..count) (values and their positions; `salt` tells arrays apart) to the
+// two 64-bit words at out (device).  The sums do not depend on the order of the additions.
+bppsa_status bppsa_launch_pattern_hash(const int32_t* a, int64_t count, unsigned long long salt,
+                                       unsigned long long* out, hipStream_t stream);
+
 constexpr int kBppsaMaxSpgemmCols = 1 << 20;  // LDS bitmap: one bit per column of B

@@ -162,6 +162,40 @@ spgemm_symbolic_kernel(int words, const int32_t* __restrict__ a_indptr,
   }
 }
 
+// ---- fingerprint of an index array ----------------------------------------------------------------
+// Each element contributes two 64-bit words, bit-mixed from (position, value, salt) with the
+// multiply-xorshift finaliser of the SplitMix64 generator; the words of all elements are summed
+// modulo 2^64, so the result is independent of the order in which waves arrive.
+__device__ __forceinline__ unsigned long long mix64(unsigned long long x) {
+  x ^= x >> 30;
+  x *= 0xbf58476d1ce4e5b9ull;
+  x ^= x >> 27;
+  x *= 0x94d049bb133111ebull;
+  x ^= x >> 31;
+  return x;
+}
+
+__global__ void __launch_bounds__(256)
+pattern_hash_kernel(const int32_t* __restrict__ a, long long count, unsigned long long salt,
+                    unsigned long long* __restrict__ out) {
+  unsigned long long h0 = 0, h1 = 0;
+  const long long stride = (long long)gridDim.x * blockDim.x;
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += stride) {
+    const unsigned long long x = ((unsigned long long)i << 32) | (unsigned int)a[i];
+    h0 += mix64(x ^ (salt * 0x9e3779b97f4a7c15ull));
+    h1 += mix64((x + salt) * 0xd1342543de82ef95ull + 1);
+  }
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) {
+    h0 += __shfl_down(h0, off, 64);
+    h1 += __shfl_down(h1, off, 64);
+  }
+  if ((threadIdx.x & 63) == 0) {
+    atomicAdd(out, h0);
+    atomicAdd(out + 1, h1);
+  }
+}
+
 // ---- numeric phase of C = A B for a known structure ---------------------------------------------
 // Every value of C is formed by ONE wave, which adds the terms of an entry in an order fixed by
 // the structure of A and B alone, so the values are the same bits on every run; no two waves ever
@@ -490,6 +524,16 @@ bppsa_status bppsa_launch_spgemm_indices(const bppsa_csr& A, const bppsa_csr& B,
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
   spgemm_symbolic_kernel<1><<<A.rows, 256, lds, stream>>>(words, A.indptr, A.indices, B.indptr, B.indices,
                                                           const_cast<int32_t*>(c_indptr), c_indices, nullptr);
+  BPPSA_CHECK_LAUNCH();
+  return BPPSA_OK;
+}
+
+bppsa_status bppsa_launch_pattern_hash(const int32_t* a, int64_t count, unsigned long long salt,
+                                       unsigned long long* out, hipStream_t stream) {
+  if (count < 1) return BPPSA_OK;
+  long long blocks = (count + 256 * 8 - 1) / (256 * 8);
+  if (blocks > 1024) blocks = 1024;
+  pattern_hash_kernel<<<(int)blocks, 256, 0, stream>>>(a, (long long)count, salt, out);
   BPPSA_CHECK_LAUNCH();
   return BPPSA_OK;
 }

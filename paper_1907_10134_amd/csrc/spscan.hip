@@ -2,16 +2,29 @@
 // hybrid schedule of Section 5.3 (a few up-sweep levels of Algorithm 1, a linear
 // scan of the block totals, the matching down-sweep levels).
 //
-// The schedule is static for a given (n, up_levels), so the host replays
-// Algorithm 1's index arithmetic symbolically once: every array slot is the
-// symbolic identity, a vector or a matrix, and each A <> B = B A becomes a
-// recorded CSR x vector or CSR x CSR step.  Steps whose result reaches no
-// requested gradient (e.g. anything built on the last array element, which
-// Algorithm 1 reads but never outputs) are dropped.  The index structures of
-// the remaining CSR x CSR products depend only on the input patterns and are
-// computed here, ahead of the training loop (Section 4.3); bppsa_spscan_run
-// then only computes values.
+// The array [seed, Jt[0], ..., Jt[n-1]] is cut into blocks of 2^up_levels elements.
+// Inside a block the elements are the leaves of a binary tree split at powers of
+// two.  The plan walks that tree on the host with symbolic operands (identity,
+// vector, matrix) and records a CSR x vector or CSR x CSR step for every product
+// A <> B = B A it needs:
+//   total(node)   = total(left) <> total(right), formed only when asked for
+//                   (up-sweep: a node of 2^(d+1) leaves is level d);
+//   spread(node)  : the left child inherits the node's exclusive prefix, the right
+//                   child gets prefix <> total(left)   (down-sweep, level d);
+//   between blocks the prefix advances serially, prefix <> total(block).
+// Totals nobody asks for (the last block's, and with it anything built on the
+// last array element, which an exclusive scan never outputs) are never planned.
+// The index structures of the CSR x CSR products depend only on the input
+// patterns and are computed when the plan is made, ahead of the training loop
+// (Section 4.3); bppsa_spscan_run then only computes values.  A
+// bppsa_spscan_cache keeps those structures in device memory of its own, keyed on
+// a fingerprint of the input patterns, so that a later plan for the same patterns
+// reuses them without running the symbolic phase again.
+#include <functional>
+#include <map>
+#include <mutex>
 #include <new>
+#include <utility>
 #include <vector>
 
 #include "bppsa_internal.h"
@@ -25,12 +38,12 @@ struct Slot { int kind; int id; };
 struct Product {          // C = left * right; ids < n are inputs, ids >= n are products
   int left, right;
   int rows, cols;
+  int level;              // the up-sweep level that forms it
   int64_t nnz;
   int64_t madds;
   int32_t* indptr;
   int32_t* indices;
   float* data;
-  bool live;
   int numeric_kind;       // which numeric kernel forms the values (chosen when the plan is built)
   int32_t* right_split;   // BLOCK kinds: where each row of the right operand crosses the column quarters
   int max_row;            // longest row of the product
@@ -40,24 +53,15 @@ struct Vec {              // id 0 is the caller's seed
   int len;
   float* buf;             // arena storage (nullptr for the seed)
   int grad_index;         // >= 0: this vector is grads[grad_index]
-  int producer;           // op index, -1 for the seed
 };
 
-enum OpKind { kSpmv = 0, kSpgemm = 1 };
 struct Op {
-  int kind;
-  int mat;                // kSpmv: matrix id;  kSpgemm: product id (>= n)
-  int vin, vout;          // kSpmv
-  bool live;
-  bool tail;              // the optional inclusive-tail product
-  bool diag = false;      // kSpmv whose matrix has exactly the entries (i, i): fused into its producer
+  int kind;               // BPPSA_STEP_SPMV or BPPSA_STEP_SPGEMM
+  int mat;                // SPMV: matrix id;  SPGEMM: product id (>= n)
+  int vin, vout;          // SPMV
+  int phase, level;
+  bool diag;              // SPMV whose matrix has exactly the entries (i, i): fused into its producer
 };
-
-int ceil_log2(int v) {
-  int l = 0;
-  while ((1 << l) < v) ++l;
-  return l;
-}
 
 }  // namespace
 
@@ -72,8 +76,6 @@ struct bppsa_spscan_plan {
   std::vector<int> grad_vec;      // vector id holding grads[k]
   size_t arena_used = 0;
   int64_t mm_flops = 0, mv_flops = 0;
-  int live_products = 0;
-  std::vector<int> live_product_ids;
 };
 
 namespace {
@@ -90,21 +92,22 @@ struct Arena {
   }
 };
 
-struct Builder {
+using AllocFn = std::function<void*(size_t)>;
+
+// The host-side walk over the tree of every block (see the head of this file).
+struct Planner {
   bppsa_spscan_plan& P;
+  const int last;                 // index of the last array element (= n)
   bool ok = true;                 // false once an operand combination outside Section 3.1 shows up
-  explicit Builder(bppsa_spscan_plan& p) : P(p) {}
+  std::map<std::pair<int, int>, Slot> totals;
+  std::vector<Slot> prefix_of;    // exclusive prefix of every array element
+  explicit Planner(bppsa_spscan_plan& p) : P(p), last(p.n), prefix_of(p.n + 1, Slot{kIdent, -1}) {}
 
   int mat_rows(int id) const { return id < P.n ? P.in_rows[id] : P.prods[id - P.n].rows; }
   int mat_cols(int id) const { return id < P.n ? P.in_cols[id] : P.prods[id - P.n].cols; }
 
-  int new_vec(int len, int producer) {
-    P.vecs.push_back(Vec{len, nullptr, -1, producer});
-    return (int)P.vecs.size() - 1;
-  }
-
   // a <> b = b a, recorded.
-  Slot combine(Slot a, Slot b) {
+  Slot combine(Slot a, Slot b, int phase, int level) {
     if (a.kind == kIdent) return b;
     if (b.kind == kIdent) return a;
     if (b.kind != kMat) {           // the right operand of <> is always a matrix (Section 3.1)
@@ -112,8 +115,9 @@ struct Builder {
       return a;
     }
     if (a.kind == kVec) {
-      const int vout = new_vec(mat_rows(b.id), (int)P.ops.size());
-      P.ops.push_back(Op{kSpmv, b.id, a.id, vout, false, false});
+      P.vecs.push_back(Vec{mat_rows(b.id), nullptr, -1});
+      const int vout = (int)P.vecs.size() - 1;
+      P.ops.push_back(Op{BPPSA_STEP_SPMV, b.id, a.id, vout, phase, level, false});
       return Slot{kVec, vout};
     }
     Product pr{};
@@ -121,30 +125,42 @@ struct Builder {
     pr.right = a.id;
     pr.rows = mat_rows(b.id);
     pr.cols = mat_cols(a.id);
+    pr.level = level;
     P.prods.push_back(pr);
     const int pid = P.n + (int)P.prods.size() - 1;
-    P.ops.push_back(Op{kSpgemm, pid, -1, -1, false, false});
+    P.ops.push_back(Op{BPPSA_STEP_SPGEMM, pid, -1, -1, phase, level, false});
     return Slot{kMat, pid};
   }
+
+  // <>-product of the elements [lo, lo + size) that exist; size is a power of two
+  Slot total(int lo, int size) {
+    if (size == 1) return lo == 0 ? Slot{kVec, 0} : Slot{kMat, lo - 1};
+    const int half = size / 2;
+    if (lo + half > last) return total(lo, half);          // nothing in the right half
+    const auto key = std::make_pair(lo, size);
+    const auto it = totals.find(key);
+    if (it != totals.end()) return it->second;
+    const Slot l = total(lo, half), r = total(lo + half, half);
+    const Slot t = combine(l, r, BPPSA_PHASE_UP, __builtin_ctz((unsigned)half));
+    totals[key] = t;
+    return t;
+  }
+
+  void spread(int lo, int size, Slot prefix) {
+    if (size == 1) {
+      prefix_of[lo] = prefix;
+      return;
+    }
+    const int half = size / 2;
+    if (lo + half > last) {
+      spread(lo, half, prefix);
+      return;
+    }
+    const Slot right_prefix = combine(prefix, total(lo, half), BPPSA_PHASE_DOWN, __builtin_ctz((unsigned)half));
+    spread(lo, half, prefix);
+    spread(lo + half, half, right_prefix);
+  }
 };
-
-void mark_mat_live(bppsa_spscan_plan& P, int id) {
-  if (id < P.n) return;
-  Product& pr = P.prods[id - P.n];
-  if (pr.live) return;
-  pr.live = true;
-  mark_mat_live(P, pr.left);
-  mark_mat_live(P, pr.right);
-}
-
-void mark_vec_live(bppsa_spscan_plan& P, int vid) {
-  const int opi = P.vecs[vid].producer;
-  if (opi < 0 || P.ops[opi].live) return;
-  Op& op = P.ops[opi];
-  op.live = true;
-  mark_mat_live(P, op.mat);
-  mark_vec_live(P, op.vin);
-}
 
 bppsa_csr mat_desc(const bppsa_spscan_plan& P, const bppsa_csr* Jt, int id) {
   if (id < P.n) return Jt[id];
@@ -152,175 +168,276 @@ bppsa_csr mat_desc(const bppsa_spscan_plan& P, const bppsa_csr* Jt, int id) {
   return bppsa_csr{pr.rows, pr.cols, pr.nnz, pr.indptr, pr.indices, pr.data};
 }
 
-}  // namespace
-
-extern "C" bppsa_status bppsa_spscan_plan_create(int n, const bppsa_csr* Jt, int up_levels,
-                                                 void* arena, size_t arena_bytes, void* stream,
-                                                 bppsa_spscan_plan** plan_out) {
-  if (!plan_out) return BPPSA_EINVAL;
-  *plan_out = nullptr;
-  if (n < 1 || !Jt || up_levels < 0 || !arena) return BPPSA_EINVAL;
-  if ((uintptr_t)arena & 255) return BPPSA_EINVAL;
+bppsa_status check_inputs(int n, const bppsa_csr* Jt, int up_levels) {
+  if (n < 1 || !Jt || up_levels < 0) return BPPSA_EINVAL;
   for (int k = 0; k < n; ++k) {
     if (Jt[k].rows < 1 || Jt[k].cols < 1 || Jt[k].nnz < 0 || !Jt[k].indptr) return BPPSA_EINVAL;
     if (Jt[k].nnz > 0 && !Jt[k].indices) return BPPSA_EINVAL;
     if (Jt[k].nnz >= INT32_MAX) return BPPSA_EOVERFLOW;
     if (k + 1 < n && Jt[k].rows != Jt[k + 1].cols) return BPPSA_ESHAPE;
   }
-  hipStream_t s = (hipStream_t)stream;
-  bppsa_spscan_plan* plan = new (std::nothrow) bppsa_spscan_plan();
-  if (!plan) return BPPSA_EINVAL;
-  bppsa_spscan_plan& P = *plan;
+  return BPPSA_OK;
+}
+
+// Fills in everything of the plan that needs no device: sizes, steps, operand ids.
+bppsa_status plan_steps(bppsa_spscan_plan& P, int n, const bppsa_csr* Jt, int up_levels) {
   P.n = n;
   for (int k = 0; k < n; ++k) {
     P.in_rows.push_back(Jt[k].rows);
     P.in_cols.push_back(Jt[k].cols);
     P.in_nnz.push_back(Jt[k].nnz);
   }
-
-  // ---- replay Algorithm 1's indices on slots --------------------------------
-  Builder B(P);
-  const int N = n;                                  // array a[0..N]
-  std::vector<Slot> a(N + 1);
-  P.vecs.push_back(Vec{Jt[0].cols, nullptr, -1, -1});   // seed
-  a[0] = Slot{kVec, 0};
-  for (int k = 1; k <= N; ++k) a[k] = Slot{kMat, k - 1};
-  const int levels = ceil_log2(N + 1);
+  int depth = 0;                                    // levels of a tree over all n + 1 elements
+  while ((1LL << depth) < (long long)n + 1) ++depth;
   int U = up_levels;
-  if (U > levels - 1) U = levels - 1;
+  if (U > depth - 1) U = depth - 1;
   if (U < 0) U = 0;
   P.up_levels = U;
-  for (int d = 0; d < U; ++d) {                     // truncated up-sweep
-    const int half = 1 << d, step = 1 << (d + 1);
-    for (int i = 0; i <= N - half; i += step) {
-      const int l = i + half - 1;
-      const int r = (i + step - 1 < N) ? i + step - 1 : N;
-      a[r] = B.combine(a[l], a[r]);
-    }
+  P.vecs.push_back(Vec{Jt[0].cols, nullptr, -1});   // the seed
+  Planner pl(P);
+  const long long block = 1LL << U;
+  Slot prefix{kIdent, -1};
+  int j = 0;
+  for (long long lo = 0; lo <= n; lo += block, ++j) {
+    pl.spread((int)lo, (int)block, prefix);
+    if (lo + block <= n) prefix = pl.combine(prefix, pl.total((int)lo, (int)block), BPPSA_PHASE_CHAIN, j);
   }
-  {                                                 // linear scan of the block totals
-    const int block = 1 << U;
-    Slot prefix{kIdent, -1};
-    for (int i = 0; i <= N; i += block) {
-      const int r = (i + block - 1 < N) ? i + block - 1 : N;
-      const Slot total = a[r];
-      a[r] = prefix;
-      if (i + block <= N) prefix = B.combine(prefix, total);
-    }
-  }
-  for (int d = U - 1; d >= 0; --d) {                // down-sweep, operands reversed
-    const int half = 1 << d, step = 1 << (d + 1);
-    for (int i = 0; i <= N - half; i += step) {
-      const int l = i + half - 1;
-      const int r = (i + step - 1 < N) ? i + step - 1 : N;
-      const Slot t = a[l];
-      a[l] = a[r];
-      a[r] = B.combine(a[r], t);
-    }
-  }
-  // a = [I, seed, grads[0], ..., grads[n-2]]; the inclusive tail needs one more product
+  if (!pl.ok) return BPPSA_EINVAL;
+  // prefixes = [I, seed, grads[0], ..., grads[n-2]]; the inclusive tail needs one more product
   P.grad_vec.assign(n, -1);
-  if (!B.ok) { delete plan; return BPPSA_EINVAL; }
-  for (int k = 0; k + 2 <= N; ++k) {
-    if (a[k + 2].kind != kVec) { delete plan; return BPPSA_EINVAL; }
-    P.grad_vec[k] = a[k + 2].id;
+  for (int k = 0; k + 2 <= n; ++k) {
+    if (pl.prefix_of[k + 2].kind != kVec) return BPPSA_EINVAL;
+    P.grad_vec[k] = pl.prefix_of[k + 2].id;
   }
   {
     const int vin = (n >= 2) ? P.grad_vec[n - 2] : 0;
-    const int vout = B.new_vec(Jt[n - 1].rows, (int)P.ops.size());
-    P.ops.push_back(Op{kSpmv, n - 1, vin, vout, false, true});
+    P.vecs.push_back(Vec{Jt[n - 1].rows, nullptr, -1});
+    const int vout = (int)P.vecs.size() - 1;
+    P.ops.push_back(Op{BPPSA_STEP_SPMV, n - 1, vin, vout, BPPSA_PHASE_TAIL, 0, false});
     P.grad_vec[n - 1] = vout;
   }
-  for (int k = 0; k < n; ++k) {
-    P.vecs[P.grad_vec[k]].grad_index = k;
-    mark_vec_live(P, P.grad_vec[k]);
-  }
-  for (Op& op : P.ops)
-    if (op.kind == kSpgemm) op.live = P.prods[op.mat - n].live;
+  for (int k = 0; k < n; ++k) P.vecs[P.grad_vec[k]].grad_index = k;
+  return BPPSA_OK;
+}
 
-  // ---- device storage and the symbolic phase of the live products ------------
-  Arena ar{static_cast<char*>(arena), arena_bytes, 0};
-  bppsa_status st = BPPSA_OK;
-  unsigned long long* d_madds = static_cast<unsigned long long*>(ar.take(sizeof(unsigned long long)));
-  if (!d_madds) st = BPPSA_EWORKSPACE;
-  for (size_t v = 1; v < P.vecs.size() && st == BPPSA_OK; ++v) {
-    const int opi = P.vecs[v].producer;
-    if (opi >= 0 && !P.ops[opi].live) continue;
-    P.vecs[v].buf = static_cast<float*>(ar.take((size_t)P.vecs[v].len * sizeof(float)));
-    if (!P.vecs[v].buf) st = BPPSA_EWORKSPACE;
-  }
-  for (size_t i = 0; i < P.prods.size() && st == BPPSA_OK; ++i) {
-    Product& pr = P.prods[i];
-    if (!pr.live) continue;
+// The symbolic phase: structure of every product, the choice of its numeric kernel, and which
+// input matrices are diagonal.  Device memory for the structures comes from `alloc`.
+bppsa_status symbolic_phase(bppsa_spscan_plan& P, const bppsa_csr* Jt, const AllocFn& alloc, hipStream_t s) {
+  const int n = P.n;
+  unsigned long long* d_madds = static_cast<unsigned long long*>(alloc(sizeof(unsigned long long)));
+  int* d_flag = static_cast<int*>(alloc(sizeof(int)));
+  if (!d_madds || !d_flag) return BPPSA_EWORKSPACE;
+  for (Product& pr : P.prods) {
     const bppsa_csr L = mat_desc(P, Jt, pr.left), R = mat_desc(P, Jt, pr.right);
-    if (L.cols != R.rows) { st = BPPSA_ESHAPE; break; }
-    pr.indptr = static_cast<int32_t*>(ar.take(((size_t)pr.rows + 1) * sizeof(int32_t)));
-    if (!pr.indptr) { st = BPPSA_EWORKSPACE; break; }
-    if (hipMemsetAsync(d_madds, 0, sizeof(unsigned long long), s) != hipSuccess) { st = BPPSA_EHIP; break; }
-    st = bppsa_launch_spgemm_count(L, R, pr.indptr, d_madds, s);
-    if (st != BPPSA_OK) break;
-    st = bppsa_lengths_to_indptr(pr.indptr, pr.rows, s);
-    if (st != BPPSA_OK) break;
-    int32_t nnz32 = 0;
+    if (L.cols != R.rows) return BPPSA_ESHAPE;
+    pr.indptr = static_cast<int32_t*>(alloc(((size_t)pr.rows + 1) * sizeof(int32_t)));
+    if (!pr.indptr) return BPPSA_EWORKSPACE;
+    if (hipMemsetAsync(d_madds, 0, sizeof(unsigned long long), s) != hipSuccess) return BPPSA_EHIP;
+    BPPSA_TRY(bppsa_launch_spgemm_count(L, R, pr.indptr, d_madds, s));
+    BPPSA_TRY(bppsa_lengths_to_indptr(pr.indptr, pr.rows, s));
+    // row pointers back to the host: nnz, and the longest row (it decides the numeric kernel)
+    std::vector<int32_t> hp((size_t)pr.rows + 1);
     unsigned long long madds = 0;
-    if (hipMemcpyAsync(&nnz32, pr.indptr + pr.rows, sizeof(int32_t), hipMemcpyDeviceToHost, s) != hipSuccess ||
+    if (hipMemcpyAsync(hp.data(), pr.indptr, hp.size() * sizeof(int32_t), hipMemcpyDeviceToHost, s) != hipSuccess ||
         hipMemcpyAsync(&madds, d_madds, sizeof(madds), hipMemcpyDeviceToHost, s) != hipSuccess ||
-        hipStreamSynchronize(s) != hipSuccess) { st = BPPSA_EHIP; break; }
-    if (nnz32 < 0) { st = BPPSA_EOVERFLOW; break; }   // a row-length sum that wrapped
-    pr.nnz = nnz32;
+        hipStreamSynchronize(s) != hipSuccess)
+      return BPPSA_EHIP;
+    if (hp[pr.rows] < 0) return BPPSA_EOVERFLOW;    // a row-length sum that wrapped
+    pr.nnz = hp[pr.rows];
     pr.madds = (int64_t)madds;
-    pr.indices = static_cast<int32_t*>(ar.take((size_t)(pr.nnz > 0 ? pr.nnz : 1) * sizeof(int32_t)));
-    pr.data = static_cast<float*>(ar.take((size_t)(pr.nnz > 0 ? pr.nnz : 1) * sizeof(float)));
-    if (!pr.indices || !pr.data) { st = BPPSA_EWORKSPACE; break; }
-    st = bppsa_launch_spgemm_indices(L, R, pr.indptr, pr.indices, s);
-    if (st != BPPSA_OK) break;
-    // the numeric kernel depends on the longest row of the product (read back once, here)
-    {
-      std::vector<int32_t> hp((size_t)pr.rows + 1);
-      if (hipMemcpyAsync(hp.data(), pr.indptr, hp.size() * sizeof(int32_t), hipMemcpyDeviceToHost, s) != hipSuccess ||
-          hipStreamSynchronize(s) != hipSuccess) { st = BPPSA_EHIP; break; }
-      int mx = 0;
-      for (int r = 0; r < pr.rows; ++r) mx = hp[r + 1] - hp[r] > mx ? hp[r + 1] - hp[r] : mx;
-      pr.max_row = mx;
-    }
+    pr.max_row = 0;
+    for (int r = 0; r < pr.rows; ++r) pr.max_row = hp[r + 1] - hp[r] > pr.max_row ? hp[r + 1] - hp[r] : pr.max_row;
+    pr.indices = static_cast<int32_t*>(alloc((size_t)(pr.nnz > 0 ? pr.nnz : 1) * sizeof(int32_t)));
+    if (!pr.indices) return BPPSA_EWORKSPACE;
+    BPPSA_TRY(bppsa_launch_spgemm_indices(L, R, pr.indptr, pr.indices, s));
     pr.numeric_kind = bppsa_spgemm_numeric_kind(pr.madds, pr.nnz, pr.max_row, R.cols);
     pr.right_split = nullptr;
     if (pr.numeric_kind >= BPPSA_SPGEMM_BLOCK_DENSE) {
-      pr.right_split = static_cast<int32_t*>(ar.take((size_t)3 * R.rows * sizeof(int32_t)));
-      if (!pr.right_split) { st = BPPSA_EWORKSPACE; break; }
-      st = bppsa_launch_row_splits(R, pr.right_split, s);
-      if (st != BPPSA_OK) break;
+      pr.right_split = static_cast<int32_t*>(alloc((size_t)3 * R.rows * sizeof(int32_t)));
+      if (!pr.right_split) return BPPSA_EWORKSPACE;
+      BPPSA_TRY(bppsa_launch_row_splits(R, pr.right_split, s));
     }
     P.mm_flops += 2 * pr.madds;
-    P.live_product_ids.push_back((int)i);
   }
   // Input matrices with the pattern of the identity (the ReLU Jacobians of Appendix D.2) are
   // recognised once, here, so that a run can apply them inside the kernel that produces
   // their operand.
-  int* d_flag = static_cast<int*>(ar.take(sizeof(int)));
-  if (!d_flag && st == BPPSA_OK) st = BPPSA_EWORKSPACE;
-  for (size_t i = 0; i < P.ops.size() && st == BPPSA_OK; ++i) {
-    Op& op = P.ops[i];
-    if (!op.live || op.kind != kSpmv || op.mat >= n) continue;
+  for (Op& op : P.ops) {
+    if (op.kind != BPPSA_STEP_SPMV || op.mat >= n) continue;
     const bppsa_csr& A = Jt[op.mat];
     if (A.rows != A.cols || A.nnz != A.rows) continue;
     int flag = 1;
-    if (hipMemcpyAsync(d_flag, &flag, sizeof(int), hipMemcpyHostToDevice, s) != hipSuccess) { st = BPPSA_EHIP; break; }
-    st = bppsa_launch_check_diagonal(A, d_flag, s);
-    if (st != BPPSA_OK) break;
+    if (hipMemcpyAsync(d_flag, &flag, sizeof(int), hipMemcpyHostToDevice, s) != hipSuccess) return BPPSA_EHIP;
+    BPPSA_TRY(bppsa_launch_check_diagonal(A, d_flag, s));
     if (hipMemcpyAsync(&flag, d_flag, sizeof(int), hipMemcpyDeviceToHost, s) != hipSuccess ||
-        hipStreamSynchronize(s) != hipSuccess) { st = BPPSA_EHIP; break; }
+        hipStreamSynchronize(s) != hipSuccess)
+      return BPPSA_EHIP;
     op.diag = flag != 0;
   }
-  if (st == BPPSA_OK && hipStreamSynchronize(s) != hipSuccess) st = BPPSA_EHIP;
-  if (st != BPPSA_OK) { delete plan; return st; }
+  if (hipStreamSynchronize(s) != hipSuccess) return BPPSA_EHIP;
   for (const Op& op : P.ops) {
-    if (!op.live || op.kind != kSpmv) continue;
-    const int64_t nnz = op.mat < n ? P.in_nnz[op.mat] : P.prods[op.mat - n].nnz;
-    if (!op.tail) P.mv_flops += 2 * nnz;
+    if (op.kind != BPPSA_STEP_SPMV || op.phase == BPPSA_PHASE_TAIL) continue;
+    P.mv_flops += 2 * (op.mat < n ? P.in_nnz[op.mat] : P.prods[op.mat - n].nnz);
+  }
+  return BPPSA_OK;
+}
+
+// Product values and intermediate vectors: one plan's own storage, from its arena.
+bppsa_status bind_values(bppsa_spscan_plan& P, Arena& ar) {
+  for (size_t v = 1; v < P.vecs.size(); ++v) {
+    P.vecs[v].buf = static_cast<float*>(ar.take((size_t)P.vecs[v].len * sizeof(float)));
+    if (!P.vecs[v].buf) return BPPSA_EWORKSPACE;
+  }
+  for (Product& pr : P.prods) {
+    pr.data = static_cast<float*>(ar.take((size_t)(pr.nnz > 0 ? pr.nnz : 1) * sizeof(float)));
+    if (!pr.data) return BPPSA_EWORKSPACE;
   }
   P.arena_used = ar.used;
-  P.live_products = (int)P.live_product_ids.size();
+  return BPPSA_OK;
+}
+
+struct CacheEntry {
+  unsigned long long key[2];
+  int up_levels_asked;
+  bppsa_spscan_plan tmpl;         // structure pointers into `blocks`; no values, no vectors bound
+  std::vector<void*> blocks;
+  ~CacheEntry() {
+    for (void* b : blocks) (void)hipFree(b);
+  }
+};
+
+}  // namespace
+
+struct bppsa_spscan_cache {
+  std::mutex mu;
+  int device = 0;
+  unsigned long long* d_key = nullptr;
+  std::vector<CacheEntry*> entries;
+  int64_t hits = 0, misses = 0, symbolic_products = 0;
+  size_t device_bytes = 0;
+};
+
+extern "C" bppsa_status bppsa_spscan_plan_create(int n, const bppsa_csr* Jt, int up_levels,
+                                                 void* arena, size_t arena_bytes, void* stream,
+                                                 bppsa_spscan_plan** plan_out) {
+  if (!plan_out) return BPPSA_EINVAL;
+  *plan_out = nullptr;
+  if (!arena || ((uintptr_t)arena & 255)) return BPPSA_EINVAL;
+  BPPSA_TRY(check_inputs(n, Jt, up_levels));
+  bppsa_spscan_plan* plan = new (std::nothrow) bppsa_spscan_plan();
+  if (!plan) return BPPSA_EINVAL;
+  Arena ar{static_cast<char*>(arena), arena_bytes, 0};
+  bppsa_status st = plan_steps(*plan, n, Jt, up_levels);
+  if (st == BPPSA_OK) st = symbolic_phase(*plan, Jt, [&](size_t bytes) { return ar.take(bytes); }, (hipStream_t)stream);
+  if (st == BPPSA_OK) st = bind_values(*plan, ar);
+  if (st != BPPSA_OK) {
+    delete plan;
+    return st;
+  }
+  *plan_out = plan;
+  return BPPSA_OK;
+}
+
+extern "C" bppsa_status bppsa_spscan_cache_create(bppsa_spscan_cache** cache_out) {
+  if (!cache_out) return BPPSA_EINVAL;
+  *cache_out = nullptr;
+  bppsa_spscan_cache* c = new (std::nothrow) bppsa_spscan_cache();
+  if (!c) return BPPSA_EINVAL;
+  if (hipGetDevice(&c->device) != hipSuccess || hipMalloc((void**)&c->d_key, 2 * sizeof(unsigned long long)) != hipSuccess) {
+    delete c;
+    return BPPSA_EHIP;
+  }
+  *cache_out = c;
+  return BPPSA_OK;
+}
+
+extern "C" void bppsa_spscan_cache_destroy(bppsa_spscan_cache* cache) {
+  if (!cache) return;
+  for (CacheEntry* e : cache->entries) delete e;
+  if (cache->d_key) (void)hipFree(cache->d_key);
+  delete cache;
+}
+
+extern "C" bppsa_status bppsa_spscan_cache_stats(bppsa_spscan_cache* cache, int64_t* hits, int64_t* misses,
+                                                 int64_t* symbolic_products, size_t* device_bytes) {
+  if (!cache) return BPPSA_EINVAL;
+  std::lock_guard<std::mutex> lock(cache->mu);
+  if (hits) *hits = cache->hits;
+  if (misses) *misses = cache->misses;
+  if (symbolic_products) *symbolic_products = cache->symbolic_products;
+  if (device_bytes) *device_bytes = cache->device_bytes;
+  return BPPSA_OK;
+}
+
+extern "C" bppsa_status bppsa_spscan_plan_create_cached(bppsa_spscan_cache* cache, int n, const bppsa_csr* Jt,
+                                                        int up_levels, void* arena, size_t arena_bytes,
+                                                        void* stream, bppsa_spscan_plan** plan_out) {
+  if (!plan_out) return BPPSA_EINVAL;
+  *plan_out = nullptr;
+  if (!cache || !arena || ((uintptr_t)arena & 255)) return BPPSA_EINVAL;
+  BPPSA_TRY(check_inputs(n, Jt, up_levels));
+  hipStream_t s = (hipStream_t)stream;
+  std::lock_guard<std::mutex> lock(cache->mu);
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) return BPPSA_EHIP;
+  if (dev != cache->device) return BPPSA_EINVAL;
+  // fingerprint of all row pointers and column indices, formed on the device
+  unsigned long long key[2] = {0, 0};
+  if (hipMemsetAsync(cache->d_key, 0, sizeof(key), s) != hipSuccess) return BPPSA_EHIP;
+  for (int k = 0; k < n; ++k) {
+    BPPSA_TRY(bppsa_launch_pattern_hash(Jt[k].indptr, (int64_t)Jt[k].rows + 1, 2ull * k + 1, cache->d_key, s));
+    if (Jt[k].nnz > 0) BPPSA_TRY(bppsa_launch_pattern_hash(Jt[k].indices, Jt[k].nnz, 2ull * k + 2, cache->d_key, s));
+  }
+  if (hipMemcpyAsync(key, cache->d_key, sizeof(key), hipMemcpyDeviceToHost, s) != hipSuccess ||
+      hipStreamSynchronize(s) != hipSuccess)
+    return BPPSA_EHIP;
+  CacheEntry* found = nullptr;
+  for (CacheEntry* e : cache->entries) {
+    if (e->key[0] != key[0] || e->key[1] != key[1] || e->tmpl.n != n || e->up_levels_asked != up_levels) continue;
+    bool same = true;
+    for (int k = 0; k < n && same; ++k)
+      same = e->tmpl.in_rows[k] == Jt[k].rows && e->tmpl.in_cols[k] == Jt[k].cols && e->tmpl.in_nnz[k] == Jt[k].nnz;
+    if (same) {
+      found = e;
+      break;
+    }
+  }
+  if (found) {
+    ++cache->hits;
+  } else {
+    ++cache->misses;
+    CacheEntry* e = new (std::nothrow) CacheEntry();
+    if (!e) return BPPSA_EINVAL;
+    e->key[0] = key[0];
+    e->key[1] = key[1];
+    e->up_levels_asked = up_levels;
+    size_t bytes = 0;
+    bppsa_status st = plan_steps(e->tmpl, n, Jt, up_levels);
+    if (st == BPPSA_OK)
+      st = symbolic_phase(e->tmpl, Jt, [&](size_t want) -> void* {
+        void* p = nullptr;
+        if (hipMalloc(&p, want) != hipSuccess) return nullptr;
+        e->blocks.push_back(p);
+        bytes += want;
+        return p;
+      }, s);
+    if (st != BPPSA_OK) {
+      delete e;
+      return st;
+    }
+    cache->symbolic_products += (int64_t)e->tmpl.prods.size();
+    cache->device_bytes += bytes;
+    cache->entries.push_back(e);
+    found = e;
+  }
+  bppsa_spscan_plan* plan = new (std::nothrow) bppsa_spscan_plan(found->tmpl);
+  if (!plan) return BPPSA_EINVAL;
+  Arena ar{static_cast<char*>(arena), arena_bytes, 0};
+  const bppsa_status st = bind_values(*plan, ar);
+  if (st != BPPSA_OK) {
+    delete plan;
+    return st;
+  }
   *plan_out = plan;
   return BPPSA_OK;
 }
@@ -332,23 +449,16 @@ extern "C" size_t bppsa_spscan_plan_arena_used(const bppsa_spscan_plan* plan) {
 }
 
 extern "C" int bppsa_spscan_plan_num_products(const bppsa_spscan_plan* plan) {
-  return plan ? plan->live_products : 0;
+  return plan ? (int)plan->prods.size() : 0;
 }
 
 extern "C" bppsa_status bppsa_spscan_plan_product(const bppsa_spscan_plan* plan, int idx, bppsa_csr* out,
                                                   int* left_id, int* right_id) {
-  if (!plan || !out || idx < 0 || idx >= plan->live_products) return BPPSA_EINVAL;
-  const Product& pr = plan->prods[plan->live_product_ids[idx]];
+  if (!plan || !out || idx < 0 || idx >= (int)plan->prods.size()) return BPPSA_EINVAL;
+  const Product& pr = plan->prods[idx];
   *out = bppsa_csr{pr.rows, pr.cols, pr.nnz, pr.indptr, pr.indices, pr.data};
-  // report operand ids with products renumbered over the live ones only
-  auto renum = [&](int id) {
-    if (id < plan->n) return id;
-    for (int k = 0; k < plan->live_products; ++k)
-      if (plan->live_product_ids[k] == id - plan->n) return plan->n + k;
-    return -1;
-  };
-  if (left_id) *left_id = renum(pr.left);
-  if (right_id) *right_id = renum(pr.right);
+  if (left_id) *left_id = pr.left;
+  if (right_id) *right_id = pr.right;
   return BPPSA_OK;
 }
 
@@ -357,6 +467,28 @@ extern "C" bppsa_status bppsa_spscan_plan_flops(const bppsa_spscan_plan* plan, i
   if (!plan) return BPPSA_EINVAL;
   if (mm_flops) *mm_flops = plan->mm_flops;
   if (mv_flops) *mv_flops = plan->mv_flops;
+  return BPPSA_OK;
+}
+
+extern "C" int bppsa_spscan_plan_num_steps(const bppsa_spscan_plan* plan) {
+  return plan ? (int)plan->ops.size() : 0;
+}
+
+extern "C" bppsa_status bppsa_spscan_plan_step_flops(const bppsa_spscan_plan* plan, int idx, bppsa_spscan_step* out) {
+  if (!plan || !out || idx < 0 || idx >= (int)plan->ops.size()) return BPPSA_EINVAL;
+  const Op& op = plan->ops[idx];
+  out->kind = op.kind;
+  out->phase = op.phase;
+  out->level = op.level;
+  out->matrix = op.mat;
+  if (op.kind == BPPSA_STEP_SPGEMM) {
+    const Product& pr = plan->prods[op.mat - plan->n];
+    out->flops = 2 * pr.madds;
+    out->numeric_kind = pr.numeric_kind;
+  } else {
+    out->flops = 2 * (op.mat < plan->n ? plan->in_nnz[op.mat] : plan->prods[op.mat - plan->n].nnz);
+    out->numeric_kind = -1;
+  }
   return BPPSA_OK;
 }
 
@@ -378,19 +510,18 @@ extern "C" bppsa_status bppsa_spscan_run(const bppsa_spscan_plan* plan, const bp
   };
   for (size_t i = 0; i < P.ops.size(); ++i) {
     const Op& op = P.ops[i];
-    if (!op.live) continue;
     bppsa_status st;
-    if (op.kind == kSpgemm) {
+    if (op.kind == BPPSA_STEP_SPGEMM) {
       const Product& pr = P.prods[op.mat - P.n];
       st = bppsa_launch_spgemm_numeric(pr.numeric_kind, mat_desc(P, Jt, pr.left), mat_desc(P, Jt, pr.right),
                                        pr.right_split, pr.indptr, pr.indices, pr.data, pr.max_row, s);
     } else {
-      if (op.tail && !grads[P.n - 1]) continue;     // inclusive tail not requested
-      // a diagonal matrix that consumes this product is applied in the same launch
-      size_t j = i + 1;
-      while (j < P.ops.size() && !P.ops[j].live) ++j;
-      const bool fuse = j < P.ops.size() && P.ops[j].kind == kSpmv && P.ops[j].diag &&
-                        P.ops[j].vin == op.vout && !(P.ops[j].tail && !grads[P.n - 1]);
+      const bool skip_tail = !grads[P.n - 1];         // inclusive tail not requested
+      if (op.phase == BPPSA_PHASE_TAIL && skip_tail) continue;
+      // a diagonal matrix that consumes this product in the next step is applied in the same launch
+      const size_t j = i + 1;
+      const bool fuse = j < P.ops.size() && P.ops[j].kind == BPPSA_STEP_SPMV && P.ops[j].diag &&
+                        P.ops[j].vin == op.vout && !(P.ops[j].phase == BPPSA_PHASE_TAIL && skip_tail);
       if (fuse) {
         st = bppsa_launch_spmv(mat_desc(P, Jt, op.mat), vec_ptr(op.vin), vec_ptr(op.vout), s,
                                Jt[P.ops[j].mat].data, vec_ptr(P.ops[j].vout));

@@ -293,3 +293,104 @@ def test_spscan_config4_products_repeat_bit_identically(bp):
             plan.product(k)[0].data.zero_()
     assert all(torch.equal(a, b) for a, b in zip(*snaps))
     plan.close()
+
+
+def _step_series(steps):
+    """(phase, level, kind) -> sorted FLOP counts, leaving out the inclusive tail."""
+    out = {}
+    for s in steps:
+        if s["phase"] != "tail":
+            out.setdefault((s["phase"], s["level"], s["kind"]), []).append(s["flops"])
+    return {k: sorted(v) for k, v in out.items()}
+
+
+@pytest.mark.parametrize("up_levels", [0, 1, 2, 3])
+def test_plan_step_flops_match_the_oracle_analysis(bp, up_levels):
+    """bppsa_spscan_plan_step_flops against counts the oracle derives from its own structural
+    products (Sections 4.3 and 5.3): the same products at the same tree levels, each with the same
+    number of multiply-adds, and totals that agree with bppsa_spscan_plan_flops."""
+    import torch
+    layers, image, label = workloads.cnn_layers(conv_channels=(3, 4, 4), pool_after=(1, 3), fc=(6, 5),
+                                                in_shape=(2, 8, 8), prune=0.5, seed=11)
+    acts32, aux = _rounded_forward(layers, image)
+    jts_ref = ocnn.network_jacobians_T(layers, acts32, aux)
+    jts = _gpu_jacobians(bp, layers, acts32)
+    arena = torch.empty((1 << 26,), dtype=torch.uint8, device="cuda")
+    plan = bp.SpscanPlan(jts, up_levels, arena)
+    steps = plan.steps()
+    ref = [{"phase": ph, "level": lv, "kind": kd, "flops": fl} for ph, lv, kd, fl in ocnn.scan_step_flops(jts_ref, up_levels)]
+    assert _step_series(steps) == _step_series(ref)
+    assert steps[-1]["phase"] == "tail" and steps[-1]["flops"] == 2 * jts_ref[-1].nnz
+    mm, mv = plan.flops()
+    assert mm == sum(s["flops"] for s in ref if s["kind"] == "mm")
+    assert mv == sum(s["flops"] for s in ref if s["kind"] == "mv")
+    assert sum(1 for s in steps if s["kind"] == "mm") == plan.num_products()
+    plan.close()
+
+
+def test_plan_step_flops_config4_two_levels(bp):
+    """configs[4] with the two up-sweep levels of Section 5.3: per-level FLOP series against the oracle."""
+    import torch
+    layers, image, label = workloads.cnn_layers()
+    acts32, aux = _rounded_forward(layers, image)
+    jts_ref = ocnn.network_jacobians_T(layers, acts32, aux)
+    jts = _gpu_jacobians(bp, layers, acts32)
+    arena = torch.empty((1 << 30,), dtype=torch.uint8, device="cuda")
+    plan = bp.SpscanPlan(jts, 2, arena)
+    ref = [{"phase": ph, "level": lv, "kind": kd, "flops": fl} for ph, lv, kd, fl in ocnn.scan_step_flops(jts_ref, 2)]
+    assert _step_series(plan.steps()) == _step_series(ref)
+    plan.close()
+
+
+def test_plan_cache_reuses_the_symbolic_phase(bp):
+    """A second plan for the same patterns comes from the cache: no product structure is computed
+    again (counted by the library), the structures are the same device arrays, and its results
+    equal those of an uncached plan; other patterns, or another level count, miss."""
+    import torch
+    layers, image, label = workloads.cnn_layers(conv_channels=(3, 4, 4), pool_after=(1, 3), fc=(6, 5),
+                                                in_shape=(2, 8, 8), prune=0.5, seed=21)
+    acts32, aux = _rounded_forward(layers, image)
+    grads_ref = ocnn.backward(layers, acts32, aux, label)
+    jts_ref = ocnn.network_jacobians_T(layers, acts32, aux)
+    jts = _gpu_jacobians(bp, layers, acts32)
+    n = len(layers)
+    seed = to_gpu(np.asarray(grads_ref[n], np.float32))
+    cache = bp.SpscanCache()
+    assert cache.stats() == (0, 0, 0, 0)
+    arenas = [torch.empty((1 << 26,), dtype=torch.uint8, device="cuda") for _ in range(3)]
+    first = bp.SpscanPlan(jts, 2, arenas[0], cache=cache)
+    hits, misses, computed, held = cache.stats()
+    assert (hits, misses) == (0, 1) and computed == first.num_products() > 0 and held > 0
+    second = bp.SpscanPlan(jts, 2, arenas[1], cache=cache)
+    assert cache.stats() == (1, 1, computed, held)
+    plain = bp.SpscanPlan(jts, 2, arenas[2])
+    assert second.arena_used() < plain.arena_used()          # structures are not in the arena
+    assert second.steps() == first.steps() == plain.steps()
+    for k in range(first.num_products()):
+        a, b = first.product(k)[0], second.product(k)[0]
+        assert a.indices.data_ptr() == b.indices.data_ptr() and a.data.data_ptr() != b.data.data_ptr()
+    outs = []
+    for plan in (first, second, plain):
+        grads = [torch.full((m.rows,), float("nan"), dtype=torch.float32, device="cuda") for m in jts]
+        plan.run(jts, seed, grads)
+        torch.cuda.synchronize()
+        outs.append(grads)
+    for k in range(n):
+        assert rel_err(to_np(outs[0][k]), np.asarray(grads_ref[n - 1 - k]).reshape(-1)) <= TOL
+        assert torch.equal(outs[0][k], outs[1][k]) and torch.equal(outs[0][k], outs[2][k])
+    _check_products(bp, second, jts_ref)
+    # same shapes and entry counts, one pattern changed: a fully connected layer whose mask is
+    # rotated by one input, so only the fingerprint of the index arrays can tell the difference
+    moved = list(jts)
+    fc_at = min(i for i, L in enumerate(reversed(layers)) if L.kind == "fc" and not L.mask.all())
+    L = list(reversed(layers))[fc_at]
+    moved[fc_at] = bp.csr_linear(to_gpu(L.weight), to_gpu(np.roll(L.mask, 1, axis=1).astype(np.uint8)))
+    assert moved[fc_at].nnz == jts[fc_at].nnz and not torch.equal(moved[fc_at].indices, jts[fc_at].indices)
+    third = bp.SpscanPlan(moved, 2, arenas[2], cache=cache)
+    assert cache.stats()[:2] == (1, 2)
+    third.close()
+    fourth = bp.SpscanPlan(jts, 1, arenas[2], cache=cache)      # another schedule: its own entry
+    assert cache.stats()[0] == 1
+    for p in (first, second, plain, fourth):
+        p.close()
+    cache.close()

@@ -170,6 +170,52 @@ def test_csr_product_is_structural_and_matches_dense_loops():
     assert np.array_equal(got_pat, pat) and np.allclose(c.toarray(), dense)
 
 
+def test_scan_step_flops_against_closed_forms_and_brute_force():
+    """The static FLOP analysis (Sections 4.3 and 5.3).  Pins: with no up-sweep level the scan is the
+    chain of matrix-vector products, 2 nnz each; fully dense operands give the textbook 2 m k n of a
+    matrix product (and 2 m k of a matrix-vector product) at the places a tree over four elements
+    must have them; on random patterns every matrix-matrix record equals a brute-force count of the
+    index triples (i, k, j) with both entries stored."""
+    dims = [5, 7, 6, 8, 4, 9, 3]                       # jts[k] is dims[k+1] x dims[k]
+    jts = [sp.random(dims[k + 1], dims[k], density=0.4, random_state=k, format="csr") for k in range(6)]
+    steps = cnn.scan_step_flops(jts, 0)
+    assert [s[:3] for s in steps] == [("linear", j, "mv") for j in range(1, 6)]
+    assert [s[3] for s in steps] == [2 * jts[k].nnz for k in range(5)]     # jts[5] only feeds the tail
+    # dense chain over 1 + 5 elements with two levels: blocks [seed, J0, J1, J2] and [J3, J4]
+    dense = [sp.csr_matrix(np.ones((dims[k + 1], dims[k]))) for k in range(5)]
+    steps = cnn.scan_step_flops(dense, 2)
+    d = dims
+    kinds = {}
+    for ph, lv, kd, fl in steps:
+        kinds.setdefault((ph, lv, kd), []).append(fl)
+    # up level 0: seed <> J0 (matrix-vector) and J1 <> J2 = J2 J1 (matrix-matrix, d3 x d2 x d1)
+    assert kinds[("up", 0, "mv")] == [2 * d[1] * d[0]]
+    assert kinds[("up", 0, "mm")] == [2 * d[3] * d[2] * d[1]]
+    # up level 1: (J0 seed) <> (J2 J1): a d3 x d1 matrix applied to a vector
+    assert kinds[("up", 1, "mv")] == [2 * d[3] * d[1]]
+    # down: inside the first block the right half's prefix is the left half's total itself (the
+    # block's own prefix is the identity: no product at level 1); the prefix of J2 is
+    # (J0 seed) <> J1 (level 0: d2 x d1); in the second block [J3, J4] the prefix of J4 is
+    # (block prefix) <> J3 (level 0: d4 x d3)
+    assert kinds[("down", 0, "mv")] == [2 * d[2] * d[1], 2 * d[4] * d[3]]
+    assert not any(k[0] == "linear" for k in kinds) and ("down", 1, "mv") not in kinds
+    assert sum(len(v) for v in kinds.values()) == 5
+    # brute force on random patterns, as many levels as the length allows
+    steps = cnn.scan_step_flops(jts, 3)
+    got_mm = sorted(f for ph, lv, kd, f in steps if kd == "mm")
+
+    def triples(a, b):
+        da, db = a.toarray() != 0, b.toarray() != 0
+        return int(sum(1 for i in range(da.shape[0]) for k in range(da.shape[1]) for j in range(db.shape[1])
+                       if da[i, k] and db[k, j]))
+    # seven elements allow at most two levels: blocks [seed, J0, J1, J2] and [J3, J4, J5].  The
+    # first block's total needs J1 <> J2 = J2 J1; in the second the prefix of J5 needs
+    # J3 <> J4 = J4 J3; nothing else multiplies two matrices
+    p21 = triples(jts[2], jts[1])
+    p43 = triples(jts[4], jts[3])
+    assert got_mm == sorted([2 * p21, 2 * p43])
+
+
 def test_full_network_shapes_and_counts():
     layers, image, label = workloads.cnn_layers()
     kinds = [L.kind for L in layers]

@@ -26,7 +26,7 @@ def test_identity_jacobians_return_seed_everywhere():
     seed = np.random.default_rng(2).standard_normal((B, H))
     G, g0 = scan.linear_scan(jt, seed)
     assert all(np.array_equal(G[t], seed) for t in range(T)) and np.array_equal(g0, seed)
-    out = scan.blelloch(scan.to_paper_array(jt, seed))
+    out = scan.tree_scan(scan.to_paper_array(jt, seed))
     assert np.array_equal(scan.from_paper_array(out), G)
 
 
@@ -63,13 +63,13 @@ def test_operand_order_is_reversed_product():
 
 
 @pytest.mark.parametrize("n", list(range(1, 131)))
-def test_blelloch_and_definition_equal_linear_scan_for_every_n(n):
+def test_tree_scan_and_definition_equal_linear_scan_for_every_n(n):
     B, H = 2, 3
     jt, seed = workloads.random_jacobian_chain(n, B, H, seed=100 + n, dtype=np.float64)
     G, _ = scan.linear_scan(jt, seed)
     a = scan.to_paper_array(jt, seed)
     counts = {}
-    out = scan.blelloch(a, counts)
+    out = scan.tree_scan(a, None, counts)
     assert out[0] is None
     Gb = scan.from_paper_array(out)
     assert np.allclose(Gb, G, rtol=1e-10, atol=1e-13)
@@ -99,8 +99,8 @@ def test_last_jacobian_never_reaches_an_output():
     jt, seed = workloads.random_jacobian_chain(9, 1, 3, seed=5, dtype=np.float64)
     jt2 = jt.copy()
     jt2[0] = 123.0                       # a[n] in the paper's array
-    G1 = scan.from_paper_array(scan.blelloch(scan.to_paper_array(jt, seed)))
-    G2 = scan.from_paper_array(scan.blelloch(scan.to_paper_array(jt2, seed)))
+    G1 = scan.from_paper_array(scan.tree_scan(scan.to_paper_array(jt, seed)))
+    G2 = scan.from_paper_array(scan.tree_scan(scan.to_paper_array(jt2, seed)))
     assert np.array_equal(G1, G2)
 
 
@@ -111,7 +111,7 @@ def test_truncated_schedule_equals_linear_scan_for_every_level_count(n):
     a = scan.to_paper_array(jt, seed)
     for U in range(0, 9):
         counts = {}
-        out = scan.blelloch_truncated(a, U, counts)
+        out = scan.tree_scan(a, U, counts)
         assert out[0] is None
         assert np.allclose(scan.from_paper_array(out), G, rtol=1e-10, atol=1e-13), (n, U)
         assert counts["down_mm"] == 0
