@@ -58,6 +58,32 @@ def rnn_inputs(T, B, H=20, I=1, C=10, seed=BASE_SEED):
     )
 
 
+def bitstream_batch(T, B, first_sample=0, seed=BASE_SEED + 7, classes=10):
+    """A mini-batch of the synthetic bit-stream classification set of Section 4.1.
+
+    Sample k (k = first_sample .. first_sample + B - 1 of the 32000 the paper synthesises) has a
+    class c drawn uniformly from 0..classes-1 and a stream x[t] ~ Bernoulli(0.05 + 0.1 c), t = 0..T-1,
+    both from a generator keyed on (seed, k), so a sample does not depend on the batch it is in.
+    Returns x [T, B, 1] float32 in {0, 1} and labels [B] int32.
+    """
+    x = np.empty((T, B, 1), np.float32)
+    labels = np.empty((B,), np.int32)
+    for j in range(B):
+        rng = np.random.Generator(np.random.Philox(key=[int(seed), int(first_sample + j)]))
+        c = int(rng.integers(0, classes))
+        labels[j] = c
+        x[:, j, 0] = rng.random(T) < (0.05 + 0.1 * c)
+    return x, labels
+
+
+def rnn_parameters(H=20, I=1, C=10, seed=BASE_SEED + 8):
+    """Initial parameters of the Section 4.1 model: every entry ~ U(-1/sqrt(H), 1/sqrt(H))."""
+    rng = _rng(seed)
+    k = 1.0 / math.sqrt(H)
+    return dict(w_ih=_uniform(rng, (H, I), k), w_hh=_uniform(rng, (H, H), k), b_ih=_uniform(rng, (H,), k),
+                b_hh=_uniform(rng, (H,), k), w_out=_uniform(rng, (C, H), k), b_out=_uniform(rng, (C,), k))
+
+
 def rnn_inputs_norm_preserving(T, B, H=20, I=1, C=10, gain=1.05, seed=BASE_SEED):
     """Test-only variant whose recurrent matrix is gain * (random orthogonal).
 
