@@ -10,6 +10,7 @@ from __future__ import annotations
 
 import argparse
 import json
+import math
 import os
 import statistics
 import sys
@@ -378,6 +379,81 @@ def cnn_workload(bp, workloads, steps):
     return res
 
 
+def train_workload(bp, workloads, T, B, reps, materialise=False):
+    """One training iteration of the Section 4.1 task (bit-stream classification, H = 20, Adam,
+    lr = 1e-5) at sequence length T and batch B: forward, head, backward as a scan, parameter
+    gradients, update.  Batches are generated on the host beforehand and resident on the GPU."""
+    import torch
+    H, I, C = 20, 1, 10
+    params = {k: torch.from_numpy(v) for k, v in workloads.rnn_parameters().items()}
+    tr = bp.RnnTrainer(T, B, H, I, C, params, materialise=materialise)
+    batches = []
+    for k in range(2):
+        x, labels = workloads.bitstream_batch(T, B, first_sample=k * B)
+        batches.append((torch.from_numpy(x).cuda(), torch.from_numpy(labels).cuda()))
+    for k in range(3):
+        tr.step(*batches[k % 2])
+    torch.cuda.synchronize()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+    for k, (a, z) in enumerate(evs):
+        a.record()
+        tr.step(*batches[k % 2])
+        z.record()
+    torch.cuda.synchronize()
+    total = statistics.median(a.elapsed_time(z) for a, z in evs)
+    assert math.isfinite(float(tr.loss.item()))
+
+    # the same calls one by one, for the breakdown (forward pass / backward pass / the rest)
+    x, labels = batches[0]
+    w_ih, w_hh = tr.view(tr.params, "w_ih"), tr.view(tr.params, "w_hh")
+    b_ih, b_hh = tr.view(tr.params, "b_ih"), tr.view(tr.params, "b_hh")
+    w_out, b_out = tr.view(tr.params, "w_out"), tr.view(tr.params, "b_out")
+    g = {k: tr.view(tr.grads, k) for k in bp.RNN_PARAM_ORDER}
+
+    def timed(fn):
+        for _ in range(2):
+            fn()
+        e = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+        for a, z in e:
+            a.record()
+            fn()
+            z.record()
+        torch.cuda.synchronize()
+        return statistics.median(a.elapsed_time(z) for a, z in e)
+
+    def backward():
+        if materialise:
+            bp.build_jacobians(bp.RNN_TANH, tr.h, w_hh=w_hh, Jt=tr.Jt)
+            bp.scan(tr.Jt, tr.seed, tr.G, workspace=tr.workspace)
+        else:
+            bp.rnn_scan_fused(tr.h, w_hh, tr.seed, tr.G, workspace=tr.workspace)
+        bp.param_grads(bp.RNN_TANH, tr.h, x, tr.G, out=(g["w_ih"], g["w_hh"], g["b_ih"], g["b_hh"]),
+                       workspace=tr.workspace)
+
+    fwd = timed(lambda: bp.forward(bp.RNN_TANH, x, w_ih, w_hh, b_ih, b_hh, tr.h))
+    head = timed(lambda: bp.head_backward(tr.h[T], w_out, b_out, labels, tr.seed, tr.loss, g["w_out"], g["b_out"]))
+    bwd = timed(backward)
+    upd = timed(lambda: bp.adam_step(tr.params, tr.grads, tr.adam_m, tr.adam_v, 5))
+    return {"T": T, "B": B, "iteration_ms": round(total, 4), "forward_ms": round(fwd, 4), "head_ms": round(head, 4),
+            "backward_ms": round(bwd, 4), "update_ms": round(upd, 4),
+            "samples_per_s": round(B / (total * 1e-3), 1)}
+
+
+def train_sweeps(bp, workloads, reps):
+    """Sequence-length and batch-size sweeps in the shape of Section 5.1's sensitivity analysis."""
+    import torch
+    out = {"task": "bitstream classification, 10 classes, Bernoulli(0.05 + 0.1 c), RNN H=20, Adam lr=1e-5",
+           "jacobians": "generated inside the scan (bppsa_rnn_scan_fused)", "by_T_at_B16": [], "by_B_at_T1000": []}
+    for T in (10, 30, 100, 300, 1000, 3000, 10000, 30000):
+        out["by_T_at_B16"].append(train_workload(bp, workloads, T, 16, reps))
+        torch.cuda.empty_cache()
+    for B in (2, 4, 8, 16, 32, 64, 128, 256):
+        out["by_B_at_T1000"].append(train_workload(bp, workloads, 1000, B, reps))
+        torch.cuda.empty_cache()
+    out["materialised_T1000_B16"] = train_workload(bp, workloads, 1000, 16, reps, materialise=True)
+    return out
+
+
 def cpu_baseline(w, budget_s=15.0):
     """The fp64 oracle's backward (chain + parameter sums) on the same workload, one thread."""
     import numpy as np
@@ -422,6 +498,8 @@ def main():
                     help="time only the T=30000 scan (for profiling); prints its JSON object")
     ap.add_argument("--gru", action="store_true",
                     help="time the three calls on configs[3] (GRU H=128, T=4096); prints its JSON object")
+    ap.add_argument("--train", action="store_true",
+                    help="whole training iterations of the Section 4.1 task over sequence lengths and batch sizes")
     ap.add_argument("--cnn", action="store_true",
                     help="time the sparse path on configs[4] (pruned CNN); prints its JSON object")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -446,6 +524,9 @@ def main():
         return
     if args.gru:
         print(json.dumps(gru_workload(bp, workloads, args.steps)))
+        return
+    if args.train:
+        print(json.dumps(train_sweeps(bp, workloads, max(5, min(30, args.steps)))))
         return
     if args.cnn:
         print(json.dumps(cnn_workload(bp, workloads, args.steps)))
@@ -535,6 +616,9 @@ def main():
         out["cnn"] = {"workload": c["workload"], "nnz": c["nnz"], "build_all_jacobians_ms": c["build_all_jacobians_ms"],
                       "up_levels_0": c["up_levels_0"], "up_levels_2": c["up_levels_2"],
                       "spmv_chain_gbps": c["spmv_chain_gbps"]}
+        torch.cuda.empty_cache()
+        # whole training iterations of the Section 4.1 task (forward + head + backward + Adam)
+        out["train"] = [train_workload(bp, workloads, 1000, 16, 20), train_workload(bp, workloads, 30000, 16, 5)]
         torch.cuda.empty_cache()
 
     if not args.no_cpu:

@@ -189,6 +189,65 @@ bppsa_status bppsa_param_grads(int cell, int T, int B, int H, int I,
 
 
 /* ------------------------------------------------------------------------
+ * One training iteration (Section 4.1): forward, head, backward as a scan,
+ * optimiser step.
+ * ---------------------------------------------------------------------- */
+
+/*
+ * bppsa_head_seed plus the head's own parameter gradients: dW_out [C,H] = dz^T h_T and
+ * db_out [C] = sum_b dz, with dz = (softmax(z) - onehot(y)) / B.  loss, dW_out and db_out may be
+ * NULL.  Sums over the batch run in index order (deterministic).  C <= 64 and B (C + 1) <= 12288.
+ */
+bppsa_status bppsa_head_backward(int B, int H, int C,
+                                 const float* h_last, const float* w_out, const float* b_out,
+                                 const int32_t* labels, float* seed, float* loss,
+                                 float* dW_out, float* db_out, void* stream);
+
+/*
+ * One Adam update of n parameters in place (Kingma & Ba, Algorithm 1; the optimiser Section 4.1
+ * trains with):  m <- beta1 m + (1 - beta1) g;  v <- beta2 v + (1 - beta2) g^2;
+ * theta <- theta - lr (m / (1 - beta1^step)) / (sqrt(v / (1 - beta2^step)) + eps).
+ * step = 1 for the first update; m and v start at zero.  All arrays are device memory.  The
+ * constants come as doubles so that 1 - beta and the two bias corrections are rounded to fp32 once.
+ */
+bppsa_status bppsa_adam_step(int64_t n, float* theta, const float* grad, float* m, float* v,
+                             int step, double lr, double beta1, double beta2, double eps, void* stream);
+
+/*
+ * The whole iteration for the tanh RNN, enqueued on `stream` without synchronising:
+ * bppsa_forward, bppsa_head_backward on h[T], the backward pass over the T steps as a scan
+ * (bppsa_build_jacobians + bppsa_scan when st->Jt is given, else bppsa_rnn_scan_fused, which
+ * exists for H = 20), bppsa_param_grads, bppsa_adam_step over all parameters.
+ * Parameters, gradients and both Adam moments are flat device arrays of
+ * bppsa_rnn_param_count(H, I, C) floats laid out as
+ *     W_ih [H,I] | W_hh [H,H] | b_ih [H] | b_hh [H] | W_out [C,H] | b_out [C].
+ * x is [T,B,I], labels [B] int32.  st->h is [T+1,B,H] with h[0] the initial state (the caller
+ * zeroes it once; rows 1..T are overwritten), st->G [T,B,H], st->seed [B,H], st->loss [1] (may be
+ * NULL), st->Jt [T,B,H,H] or NULL, st->workspace of at least
+ * bppsa_rnn_train_workspace_bytes(T, B, H, I) bytes, 256-byte aligned.  The struct is host memory,
+ * its pointers device memory; nothing is allocated.  st->loss receives the loss before the update.
+ */
+typedef struct bppsa_rnn_train_state {
+  float* params;
+  float* grads;
+  float* adam_m;
+  float* adam_v;
+  float* h;
+  float* G;
+  float* seed;
+  float* loss;
+  float* Jt;
+  void* workspace;
+  size_t workspace_bytes;
+} bppsa_rnn_train_state;
+size_t bppsa_rnn_param_count(int H, int I, int C);
+size_t bppsa_rnn_train_workspace_bytes(int T, int B, int H, int I);
+bppsa_status bppsa_rnn_train_step(int T, int B, int H, int I, int C,
+                                  const float* x, const int32_t* labels,
+                                  const bppsa_rnn_train_state* st, int step,
+                                  double lr, double beta1, double beta2, double eps, void* stream);
+
+/* ------------------------------------------------------------------------
  * Sparse path: CSR transposed Jacobians of a (pruned) CNN and their scan.
  * ---------------------------------------------------------------------- */
 

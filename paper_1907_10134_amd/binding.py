@@ -84,6 +84,18 @@ def _load(path=_LIB_PATH):
     lib.bppsa_spscan_plan_flops.restype = c_int
     lib.bppsa_spscan_plan_flops.argtypes = [c_void_p, ctypes.POINTER(ctypes.c_int64),
                                             ctypes.POINTER(ctypes.c_int64)]
+    c_double = ctypes.c_double
+    lib.bppsa_head_backward.restype = c_int
+    lib.bppsa_head_backward.argtypes = [c_int] * 3 + [c_void_p] * 8 + [c_void_p]
+    lib.bppsa_adam_step.restype = c_int
+    lib.bppsa_adam_step.argtypes = [ctypes.c_int64] + [c_void_p] * 4 + [c_int] + [c_double] * 4 + [c_void_p]
+    lib.bppsa_rnn_param_count.restype = c_size_t
+    lib.bppsa_rnn_param_count.argtypes = [c_int] * 3
+    lib.bppsa_rnn_train_workspace_bytes.restype = c_size_t
+    lib.bppsa_rnn_train_workspace_bytes.argtypes = [c_int] * 4
+    lib.bppsa_rnn_train_step.restype = c_int
+    lib.bppsa_rnn_train_step.argtypes = [c_int] * 5 + [c_void_p, c_void_p, ctypes.POINTER(RnnTrainState), c_int] + \
+        [c_double] * 4 + [c_void_p]
     lib.bppsa_spscan_plan_num_steps.restype = c_int
     lib.bppsa_spscan_plan_num_steps.argtypes = [c_void_p]
     lib.bppsa_spscan_plan_step_flops.restype = c_int
@@ -113,6 +125,12 @@ class CsrDesc(ctypes.Structure):
     """Mirror of the C struct bppsa_csr (host struct, device array pointers)."""
     _fields_ = [("rows", ctypes.c_int32), ("cols", ctypes.c_int32), ("nnz", ctypes.c_int64),
                 ("indptr", ctypes.c_void_p), ("indices", ctypes.c_void_p), ("data", ctypes.c_void_p)]
+
+
+class RnnTrainState(ctypes.Structure):
+    """Mirror of the C struct bppsa_rnn_train_state (host struct, device pointers)."""
+    _fields_ = [(k, ctypes.c_void_p) for k in ("params", "grads", "adam_m", "adam_v", "h", "G", "seed", "loss",
+                                                "Jt", "workspace")] + [("workspace_bytes", ctypes.c_size_t)]
 
 
 class SpscanStep(ctypes.Structure):
@@ -277,6 +295,92 @@ def param_grads(cell, h, x, G, w_ih=None, w_hh=None, b_ih=None, b_hh=None, out=N
                                   workspace.numel() * workspace.element_size(), _stream(stream)),
            "bppsa_param_grads")
     return out
+
+
+# --------------------------------------------------------------------------
+# Training iteration
+# --------------------------------------------------------------------------
+
+def head_backward(h_last, w_out, b_out, labels, seed=None, loss=None, dW_out=None, db_out=None, stream=None):
+    """bppsa_head_backward: (seed, loss, dW_out, db_out) of the softmax cross-entropy head."""
+    B, H = h_last.shape
+    C = w_out.shape[0]
+    dev = h_last.device
+    seed = torch.empty((B, H), dtype=torch.float32, device=dev) if seed is None else seed
+    loss = torch.empty((1,), dtype=torch.float32, device=dev) if loss is None else loss
+    dW_out = torch.empty((C, H), dtype=torch.float32, device=dev) if dW_out is None else dW_out
+    db_out = torch.empty((C,), dtype=torch.float32, device=dev) if db_out is None else db_out
+    _check(_lib.bppsa_head_backward(B, H, C, _ptr(h_last), _ptr(w_out), _ptr(b_out), _ptr(labels, torch.int32),
+                                    _ptr(seed), _ptr(loss), _ptr(dW_out), _ptr(db_out), _stream(stream)),
+           "bppsa_head_backward")
+    return seed, loss, dW_out, db_out
+
+
+def adam_step(theta, grad, m, v, step, lr=1e-5, beta1=0.9, beta2=0.999, eps=1e-8, stream=None):
+    """bppsa_adam_step: in-place update of theta, m, v (flat fp32 tensors of equal length)."""
+    _check(_lib.bppsa_adam_step(theta.numel(), _ptr(theta), _ptr(grad), _ptr(m), _ptr(v), int(step), lr, beta1,
+                                beta2, eps, _stream(stream)), "bppsa_adam_step")
+    return theta
+
+
+def rnn_param_count(H, I, C):
+    return int(_lib.bppsa_rnn_param_count(H, I, C))
+
+
+RNN_PARAM_ORDER = ("w_ih", "w_hh", "b_ih", "b_hh", "w_out", "b_out")
+
+
+def rnn_param_shapes(H, I, C):
+    return {"w_ih": (H, I), "w_hh": (H, H), "b_ih": (H,), "b_hh": (H,), "w_out": (C, H), "b_out": (C,)}
+
+
+class RnnTrainer:
+    """Device buffers of bppsa_rnn_train_step for fixed (T, B, H, I, C); step() enqueues one iteration.
+
+    params / grads / adam_m / adam_v are flat tensors in the library's layout (views(name) gives the
+    shaped view of one parameter); with materialise=False the H = 20 scan generates the Jacobians
+    itself and no Jt buffer exists."""
+
+    def __init__(self, T, B, H, I, C, params, materialise=True, device="cuda"):
+        self.dims = (T, B, H, I, C)
+        n = rnn_param_count(H, I, C)
+        f32 = dict(dtype=torch.float32, device=device)
+        self.params = torch.cat([params[k].reshape(-1).to(**f32) for k in RNN_PARAM_ORDER]).contiguous()
+        assert self.params.numel() == n
+        self.grads = torch.zeros((n,), **f32)
+        self.adam_m = torch.zeros((n,), **f32)
+        self.adam_v = torch.zeros((n,), **f32)
+        self.h = torch.zeros((T + 1, B, H), **f32)
+        self.G = torch.empty((T, B, H), **f32)
+        self.seed = torch.empty((B, H), **f32)
+        self.loss = torch.zeros((1,), **f32)
+        self.Jt = torch.empty((T, B, H, H), **f32) if materialise else None
+        self.workspace = _workspace(int(_lib.bppsa_rnn_train_workspace_bytes(T, B, H, I)), torch.device(device))
+        self.t = 0
+        self._st = RnnTrainState(self.params.data_ptr(), self.grads.data_ptr(), self.adam_m.data_ptr(),
+                                 self.adam_v.data_ptr(), self.h.data_ptr(), self.G.data_ptr(), self.seed.data_ptr(),
+                                 self.loss.data_ptr(), self.Jt.data_ptr() if materialise else None,
+                                 self.workspace.data_ptr(), self.workspace.numel() * self.workspace.element_size())
+
+    def view(self, flat, name):
+        T, B, H, I, C = self.dims
+        off = 0
+        for k in RNN_PARAM_ORDER:
+            shape = rnn_param_shapes(H, I, C)[k]
+            size = 1
+            for d in shape:
+                size *= d
+            if k == name:
+                return flat[off:off + size].view(shape)
+            off += size
+        raise KeyError(name)
+
+    def step(self, x, labels, lr=1e-5, beta1=0.9, beta2=0.999, eps=1e-8, stream=None):
+        T, B, H, I, C = self.dims
+        self.t += 1
+        _check(_lib.bppsa_rnn_train_step(T, B, H, I, C, _ptr(x), _ptr(labels, torch.int32), ctypes.byref(self._st),
+                                         self.t, lr, beta1, beta2, eps, _stream(stream)), "bppsa_rnn_train_step")
+        return self.loss
 
 
 # --------------------------------------------------------------------------
