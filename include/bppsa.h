@@ -285,6 +285,27 @@ bppsa_status bppsa_csr_conv3x3_fill(int ci, int co, int h, int w, const float* w
                                     int32_t* indices, float* data, void* stream);
 
 /*
+ * The same for a convolution of any kernel size, stride, zero padding and dilation (the generic
+ * routine the footnote of Appendix D.1 leaves open): weight [co,ci,kh,kw] on a ci x h x w input,
+ * output co x oh x ow with oh = (h + 2 pad_h - dil_h (kh - 1) - 1) / stride_h + 1 (ow alike).
+ * Row (ci,y,x) holds column (co*oh + oy)*ow + ox with value weight[co][ci][ky][kx] wherever
+ * y = oy stride_h - pad_h + ky dil_h and x = ox stride_w - pad_w + kx dil_w; an input and an output
+ * meet through at most one tap, so no entry is a sum; columns ascend.  mask [co,ci,kh,kw] as
+ * above.  With kh = kw = 3, stride 1, padding 1, dilation 1 the arrays equal those of
+ * bppsa_csr_conv3x3_*.  BPPSA_ESHAPE if the dilated kernel is larger than the padded image,
+ * BPPSA_EOVERFLOW if a size or co*oh*ow*ci*kh*kw does not fit 32 bits.  The same two calls;
+ * indptr has ci*h*w + 1 entries.  The geometry struct is host memory.
+ */
+typedef struct bppsa_conv2d_geometry {
+  int32_t kh, kw, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w;
+} bppsa_conv2d_geometry;
+bppsa_status bppsa_csr_conv2d_indptr(int ci, int co, int h, int w, const bppsa_conv2d_geometry* geometry,
+                                     const uint8_t* mask, int32_t* indptr, void* stream);
+bppsa_status bppsa_csr_conv2d_fill(int ci, int co, int h, int w, const bppsa_conv2d_geometry* geometry,
+                                   const float* weight, const uint8_t* mask, const int32_t* indptr,
+                                   int32_t* indices, float* data, void* stream);
+
+/*
  * Appendix D.2 (Algorithms 5-7): ReLU on d elements.  indptr[i] = i,
  * indices[i] = i, data[i] = (x[i] > 0) ? 1 : 0 (explicit zeros are kept).
  * indptr [d+1], indices [d], data [d].

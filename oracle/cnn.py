@@ -19,6 +19,10 @@ Two independent things live here.
    stores one unit entry per output at the first maximum of its window in
    row-major window order.
 
+`conv2d` / `conv2d_jacobian_T` are the same pair for a convolution with any kernel size, stride,
+zero padding and dilation (the generic routine Appendix D.1's footnote leaves open), written as
+the definition's loops.
+
 `csr_product` is the structural product: its pattern is the boolean product of
 the patterns (explicit zeros propagate, nothing is dropped by value).
 
@@ -27,7 +31,9 @@ Pins (tests/test_oracle_cnn.py): Table 1's sparsity values and the 768 MB /
 dense Jacobians obtained by pushing unit impulses / finite differences through
 `forward` on tiny shapes; finite differences of the loss for `backward`;
 `CSR -> dense . g` equals `backward`'s layer rule; dense triple loops for
-`csr_product`.
+`csr_product`; `conv2d` against SciPy's 2-D correlation where stride and dilation are 1 and
+against `conv3x3`; `conv2d_jacobian_T` against unit impulses pushed through `conv2d` and, for the
+3x3 / padding 1 case, against `conv_jacobian_T` (itself pinned to Table 1).
 """
 from __future__ import annotations
 
@@ -212,6 +218,64 @@ def conv_jacobian_T(w, mask, h, wd):
         return sp.csr_matrix((ci * h * wd, co * h * wd))
     return _canonical(np.concatenate(rows), np.concatenate(cols), np.concatenate(vals),
                       (ci * h * wd, co * h * wd))
+
+
+def conv2d_out_size(n, k, stride, pad, dil):
+    """Number of output positions along one axis of a convolution (0 if the kernel does not fit)."""
+    span = n + 2 * pad - dil * (k - 1) - 1
+    return span // stride + 1 if span >= 0 else 0
+
+
+def conv2d(x, w, stride=(1, 1), padding=(0, 0), dilation=(1, 1)):
+    """Cross-correlation with any kernel size, stride, zero padding and dilation, from its definition:
+    out[o, oy, ox] = sum_{c, ky, kx} w[o, c, ky, kx] x[c, oy sh - ph + ky dh, ox sw - pw + kx dw]."""
+    x, w = _f64(x), _f64(w)
+    ci, h, wd = x.shape
+    co, _, kh, kw = w.shape
+    (sh, sw), (ph, pw), (dh, dw) = stride, padding, dilation
+    oh, ow = conv2d_out_size(h, kh, sh, ph, dh), conv2d_out_size(wd, kw, sw, pw, dw)
+    out = np.zeros((co, oh, ow))
+    for oy in range(oh):
+        for ox in range(ow):
+            for ky in range(kh):
+                for kx in range(kw):
+                    y, xx = oy * sh - ph + ky * dh, ox * sw - pw + kx * dw
+                    if 0 <= y < h and 0 <= xx < wd:
+                        out[:, oy, ox] += w[:, :, ky, kx] @ x[:, y, xx]
+    return out
+
+
+def conv2d_jacobian_T(w, mask, h, wd, stride=(1, 1), padding=(0, 0), dilation=(1, 1)):
+    """Transposed Jacobian of `conv2d` (the generic routine the footnote of Appendix D.1 leaves open):
+    rows (c, y, x), columns (o, oy, ox); entry w[o, c, ky, kx] wherever y = oy sh - ph + ky dh and
+    x = ox sw - pw + kx dw for a kept (mask) weight.  One input/output pair meets through at most
+    one tap, so no entry is a sum.  Canonical CSR, pruned weights structurally absent."""
+    w = _f64(w)
+    co, ci, kh, kw = w.shape
+    mask = np.ones(w.shape, bool) if mask is None else np.asarray(mask, bool)
+    (sh, sw), (ph, pw), (dh, dw) = stride, padding, dilation
+    oh, ow = conv2d_out_size(h, kh, sh, ph, dh), conv2d_out_size(wd, kw, sw, pw, dw)
+    rows, cols, vals = [], [], []
+    for o in range(co):
+        for c in range(ci):
+            for ky in range(kh):
+                for kx in range(kw):
+                    if not mask[o, c, ky, kx]:
+                        continue
+                    for oy in range(oh):
+                        y = oy * sh - ph + ky * dh
+                        if not 0 <= y < h:
+                            continue
+                        for ox in range(ow):
+                            x = ox * sw - pw + kx * dw
+                            if 0 <= x < wd:
+                                rows.append((c * h + y) * wd + x)
+                                cols.append((o * oh + oy) * ow + ox)
+                                vals.append(w[o, c, ky, kx])
+    shape = (ci * h * wd, co * oh * ow)
+    if not rows:
+        return sp.csr_matrix(shape)
+    return _canonical(np.asarray(rows), np.asarray(cols), np.asarray(vals), shape)
 
 
 def relu_jacobian_T(x):

@@ -59,6 +59,10 @@ def _load(path=_LIB_PATH):
     lib.bppsa_csr_conv3x3_indptr.argtypes = [c_int] * 4 + [c_void_p] * 3
     lib.bppsa_csr_conv3x3_fill.restype = c_int
     lib.bppsa_csr_conv3x3_fill.argtypes = [c_int] * 4 + [c_void_p] * 6
+    lib.bppsa_csr_conv2d_indptr.restype = c_int
+    lib.bppsa_csr_conv2d_indptr.argtypes = [c_int] * 4 + [ctypes.POINTER(Conv2dGeometry)] + [c_void_p] * 3
+    lib.bppsa_csr_conv2d_fill.restype = c_int
+    lib.bppsa_csr_conv2d_fill.argtypes = [c_int] * 4 + [ctypes.POINTER(Conv2dGeometry)] + [c_void_p] * 6
     lib.bppsa_csr_relu.restype = c_int
     lib.bppsa_csr_relu.argtypes = [c_int] + [c_void_p] * 5
     lib.bppsa_csr_maxpool2x2.restype = c_int
@@ -125,6 +129,11 @@ class CsrDesc(ctypes.Structure):
     """Mirror of the C struct bppsa_csr (host struct, device array pointers)."""
     _fields_ = [("rows", ctypes.c_int32), ("cols", ctypes.c_int32), ("nnz", ctypes.c_int64),
                 ("indptr", ctypes.c_void_p), ("indices", ctypes.c_void_p), ("data", ctypes.c_void_p)]
+
+
+class Conv2dGeometry(ctypes.Structure):
+    """Mirror of the C struct bppsa_conv2d_geometry."""
+    _fields_ = [(k, ctypes.c_int32) for k in ("kh", "kw", "stride_h", "stride_w", "pad_h", "pad_w", "dil_h", "dil_w")]
 
 
 class RnnTrainState(ctypes.Structure):
@@ -428,6 +437,23 @@ def csr_conv3x3(weight, mask, h, w, stream=None):
         lambda ip, ix, d: _check(_lib.bppsa_csr_conv3x3_fill(ci, co, h, w, _ptr(weight), mp,
                                                              _ptr(ip, torch.int32), _ptr(ix, torch.int32),
                                                              _ptr(d), st), "bppsa_csr_conv3x3_fill"))
+
+
+def csr_conv2d(weight, mask, h, w, stride=(1, 1), padding=(0, 0), dilation=(1, 1), stream=None):
+    """bppsa_csr_conv2d_indptr + _fill.  weight [co,ci,kh,kw] fp32, mask same shape uint8 or None."""
+    co, ci, kh, kw = weight.shape
+    g = Conv2dGeometry(kh, kw, stride[0], stride[1], padding[0], padding[1], dilation[0], dilation[1])
+    oh = (h + 2 * padding[0] - dilation[0] * (kh - 1) - 1) // stride[0] + 1
+    ow = (w + 2 * padding[1] - dilation[1] * (kw - 1) - 1) // stride[1] + 1
+    st = _stream(stream)
+    mp = _ptr(mask, torch.uint8, "mask")
+    return _two_call(
+        ci * h * w, co * max(oh, 0) * max(ow, 0), weight.device,
+        lambda ip: _check(_lib.bppsa_csr_conv2d_indptr(ci, co, h, w, ctypes.byref(g), mp, _ptr(ip, torch.int32), st),
+                          "bppsa_csr_conv2d_indptr"),
+        lambda ip, ix, d: _check(_lib.bppsa_csr_conv2d_fill(ci, co, h, w, ctypes.byref(g), _ptr(weight), mp,
+                                                            _ptr(ip, torch.int32), _ptr(ix, torch.int32),
+                                                            _ptr(d), st), "bppsa_csr_conv2d_fill"))
 
 
 def csr_linear(weight, mask, stream=None):

@@ -1,5 +1,6 @@
 // Analytic generation of transposed Jacobians directly in CSR (Appendix D):
-// 3x3 convolution, ReLU, 2x2 max-pooling and the fully connected layer.
+// 3x3 convolution (and the convolution of any kernel size, stride, padding and dilation), ReLU,
+// 2x2 max-pooling and the fully connected layer.
 // Row pointers come from a count pass plus an exclusive prefix sum; column
 // indices within a row ascend because candidates are enumerated in column order
 // and compacted with wave-level prefix counts.
@@ -57,6 +58,86 @@ conv_rows_kernel(int ci, int co, int h, int w, const float* __restrict__ weight,
     count += __popcll(bal);
   }
   if (!FILL && lane == 0) indptr[row] = count;
+}
+
+// Any kernel size, stride, zero padding and dilation (the generic routine the footnote of Appendix
+// D.1 leaves open).  Input (c, y, x) feeds output (o, oy, ox) through tap (ky, kx) when
+// y = oy sh - ph + ky dh and x = ox sw - pw + kx dw; for a given output the tap is unique, so
+// no entry is a sum.  Candidate q = o * kh * kw + tap with the taps taken from the last to the
+// first, which makes (oy, ox) and with it the column ascend along a row.
+struct ConvGeom {
+  int kh, kw, sh, sw, ph, pw, dh, dw, oh, ow;
+};
+
+__device__ __forceinline__ ConvCand conv2d_candidate(int q, int c, int y, int x, int ci, const ConvGeom& g,
+                                                     const uint8_t* __restrict__ mask) {
+  ConvCand r;
+  const int taps = g.kh * g.kw;
+  const int o = q / taps, tap = q - o * taps;
+  const int ky = g.kh - 1 - tap / g.kw, kx = g.kw - 1 - (tap - (tap / g.kw) * g.kw);
+  const int ny = y + g.ph - ky * g.dh, nx = x + g.pw - kx * g.dw;      // oy sh and ox sw
+  const int oy = ny / g.sh, ox = nx / g.sw;
+  r.widx = ((o * ci + c) * g.kh + ky) * g.kw + kx;
+  r.col = (o * g.oh + oy) * g.ow + ox;
+  r.valid = ny >= 0 && nx >= 0 && oy * g.sh == ny && ox * g.sw == nx && oy < g.oh && ox < g.ow &&
+            (mask == nullptr || mask[r.widx] != 0);
+  return r;
+}
+
+template <int FILL>
+__global__ void __launch_bounds__(256)
+conv2d_rows_kernel(int ci, int co, int h, int w, ConvGeom g, const float* __restrict__ weight,
+                   const uint8_t* __restrict__ mask, int32_t* __restrict__ indptr,
+                   int32_t* __restrict__ indices, float* __restrict__ data) {
+  const int lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int rows = ci * h * w;
+  if (row >= rows) return;
+  const int c = row / (h * w);
+  const int rem = row - c * h * w;
+  const int y = rem / w, x = rem - y * w;
+  const int ncand = co * g.kh * g.kw;
+  int count = 0;
+  const int base = FILL ? indptr[row] : 0;
+  for (int q0 = 0; q0 < ncand; q0 += 64) {
+    const int q = q0 + lane;
+    ConvCand cd;
+    cd.valid = false;
+    if (q < ncand) cd = conv2d_candidate(q, c, y, x, ci, g, mask);
+    const unsigned long long bal = __ballot(cd.valid);
+    if (FILL && cd.valid) {
+      const int off = count + __popcll(bal & ((1ull << lane) - 1ull));
+      indices[base + off] = cd.col;
+      data[base + off] = weight[cd.widx];
+    }
+    count += __popcll(bal);
+  }
+  if (!FILL && lane == 0) indptr[row] = count;
+}
+
+// host: checks the geometry, fills in the output size; false if a size does not fit 32 bits
+bppsa_status conv2d_geometry(int ci, int co, int h, int w, const bppsa_conv2d_geometry* in, ConvGeom* g) {
+  if (!in || ci < 1 || co < 1 || h < 1 || w < 1) return BPPSA_EINVAL;
+  if (in->kh < 1 || in->kw < 1 || in->stride_h < 1 || in->stride_w < 1 || in->pad_h < 0 || in->pad_w < 0 ||
+      in->dil_h < 1 || in->dil_w < 1)
+    return BPPSA_EINVAL;
+  const int64_t span_h = (int64_t)h + 2LL * in->pad_h - (int64_t)in->dil_h * (in->kh - 1) - 1;
+  const int64_t span_w = (int64_t)w + 2LL * in->pad_w - (int64_t)in->dil_w * (in->kw - 1) - 1;
+  if (span_h < 0 || span_w < 0) return BPPSA_ESHAPE;               // the kernel does not fit: no output
+  const int64_t oh = span_h / in->stride_h + 1, ow = span_w / in->stride_w + 1;
+  const int64_t rows = (int64_t)ci * h * w, cols = (int64_t)co * oh * ow;
+  const int64_t taps = (int64_t)in->kh * in->kw;
+  if (rows >= INT32_MAX || cols >= INT32_MAX || taps >= INT32_MAX || (int64_t)co * taps >= INT32_MAX ||
+      (int64_t)co * ci * taps >= INT32_MAX)
+    return BPPSA_EOVERFLOW;
+  // every stored entry is one (output element, input channel, tap) triple
+  if ((double)cols * (double)ci * (double)taps >= (double)INT32_MAX) return BPPSA_EOVERFLOW;
+  // intermediate coordinates: y + pad and ky * dil
+  if ((int64_t)h + in->pad_h >= INT32_MAX || (int64_t)w + in->pad_w >= INT32_MAX ||
+      (int64_t)in->dil_h * in->kh >= INT32_MAX || (int64_t)in->dil_w * in->kw >= INT32_MAX)
+    return BPPSA_EOVERFLOW;
+  *g = ConvGeom{in->kh, in->kw, in->stride_h, in->stride_w, in->pad_h, in->pad_w, in->dil_h, in->dil_w, (int)oh, (int)ow};
+  return BPPSA_OK;
 }
 
 template <int FILL>
@@ -151,6 +232,30 @@ extern "C" bppsa_status bppsa_csr_conv3x3_fill(int ci, int co, int h, int w, con
   if (rows >= INT32_MAX || (int64_t)co * h * w >= INT32_MAX || nnz_max >= INT32_MAX) return BPPSA_EOVERFLOW;
   conv_rows_kernel<1><<<bppsa_ceil_div((int)rows, 4), 256, 0, (hipStream_t)stream>>>(
       ci, co, h, w, weight, mask, const_cast<int32_t*>(indptr), indices, data);
+  BPPSA_CHECK_LAUNCH();
+  return BPPSA_OK;
+}
+
+extern "C" bppsa_status bppsa_csr_conv2d_indptr(int ci, int co, int h, int w, const bppsa_conv2d_geometry* geometry,
+                                                const uint8_t* mask, int32_t* indptr, void* stream) {
+  if (!indptr) return BPPSA_EINVAL;
+  ConvGeom g;
+  BPPSA_TRY(conv2d_geometry(ci, co, h, w, geometry, &g));
+  const int rows = ci * h * w;
+  hipStream_t s = (hipStream_t)stream;
+  conv2d_rows_kernel<0><<<bppsa_ceil_div(rows, 4), 256, 0, s>>>(ci, co, h, w, g, nullptr, mask, indptr, nullptr, nullptr);
+  BPPSA_CHECK_LAUNCH();
+  return bppsa_lengths_to_indptr(indptr, rows, s);
+}
+
+extern "C" bppsa_status bppsa_csr_conv2d_fill(int ci, int co, int h, int w, const bppsa_conv2d_geometry* geometry,
+                                              const float* weight, const uint8_t* mask, const int32_t* indptr,
+                                              int32_t* indices, float* data, void* stream) {
+  if (!weight || !indptr || !indices || !data) return BPPSA_EINVAL;
+  ConvGeom g;
+  BPPSA_TRY(conv2d_geometry(ci, co, h, w, geometry, &g));
+  conv2d_rows_kernel<1><<<bppsa_ceil_div(ci * h * w, 4), 256, 0, (hipStream_t)stream>>>(
+      ci, co, h, w, g, weight, mask, const_cast<int32_t*>(indptr), indices, data);
   BPPSA_CHECK_LAUNCH();
   return BPPSA_OK;
 }

@@ -80,6 +80,21 @@ def test_bad_arguments_are_rejected_before_any_launch(lib):
     assert lib.bppsa_csr_maxpool2x2(1, 3, 4, one, one, one, one, null) == ESHAPE
     lib.bppsa_csr_conv3x3_indptr.argtypes = [ctypes.c_int] * 4 + [ctypes.c_void_p] * 3
     assert lib.bppsa_csr_conv3x3_indptr(4096, 4096, 64, 64, null, one, null) == EOVERFLOW
+    geom = (ctypes.c_int32 * 8)
+    lib.bppsa_csr_conv2d_indptr.argtypes = [ctypes.c_int] * 4 + [ctypes.c_void_p] * 4
+    assert lib.bppsa_csr_conv2d_indptr(1, 1, 8, 8, null, null, one, null) == EINVAL                   # no geometry
+    assert lib.bppsa_csr_conv2d_indptr(1, 1, 8, 8, geom(3, 3, 0, 1, 1, 1, 1, 1), null, one, null) == EINVAL   # stride 0
+    assert lib.bppsa_csr_conv2d_indptr(1, 1, 8, 8, geom(3, 3, 1, 1, -1, 0, 1, 1), null, one, null) == EINVAL  # negative padding
+    assert lib.bppsa_csr_conv2d_indptr(1, 1, 4, 4, geom(7, 7, 1, 1, 0, 0, 1, 1), null, one, null) == ESHAPE   # kernel larger than the image
+    assert lib.bppsa_csr_conv2d_indptr(1, 1, 8, 8, geom(3, 3, 1, 1, 0, 0, 4, 1), null, one, null) == ESHAPE   # dilated kernel too tall
+    assert lib.bppsa_csr_conv2d_indptr(512, 512, 64, 64, geom(5, 5, 1, 1, 2, 2, 1, 1), null, one, null) == EOVERFLOW
+    lib.bppsa_adam_step.argtypes = [ctypes.c_int64] + [ctypes.c_void_p] * 4 + [ctypes.c_int] + [ctypes.c_double] * 4 + [ctypes.c_void_p]
+    assert lib.bppsa_adam_step(10, one, one, one, one, 0, 1e-5, 0.9, 0.999, 1e-8, null) == EINVAL     # steps count from 1
+    assert lib.bppsa_adam_step(10, one, one, one, one, 1, 1e-5, 1.0, 0.999, 1e-8, null) == EINVAL     # beta1 = 1
+    lib.bppsa_head_backward.argtypes = [ctypes.c_int] * 3 + [ctypes.c_void_p] * 9
+    assert lib.bppsa_head_backward(4000, 20, 10, one, one, one, one, one, null, null, null, null) == ESHAPE
+    lib.bppsa_rnn_param_count.restype = ctypes.c_size_t
+    assert lib.bppsa_rnn_param_count(20, 1, 10) == 20 + 400 + 40 + 200 + 10
     lib.bppsa_head_seed.argtypes = [ctypes.c_int] * 3 + [ctypes.c_void_p] * 7
     assert lib.bppsa_head_seed(1, 4, 65, one, one, one, one, one, null, null) == ESHAPE
     lib.bppsa_rnn_scan_fused.argtypes = [ctypes.c_int] * 3 + [ctypes.c_void_p] * 6 + [ctypes.c_size_t, ctypes.c_void_p]

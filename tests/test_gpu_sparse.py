@@ -394,3 +394,78 @@ def test_plan_cache_reuses_the_symbolic_phase(bp):
     for p in (first, second, plain, fourth):
         p.close()
     cache.close()
+
+
+CONV_GEOMETRIES = [  # (ci, co, h, w, kh, kw, stride, padding, dilation, keep)
+    (2, 3, 5, 6, 3, 3, (1, 1), (1, 1), (1, 1), 0.7),
+    (1, 2, 7, 5, 5, 3, (2, 1), (2, 0), (1, 1), 1.0),
+    (2, 2, 8, 8, 2, 2, (2, 2), (0, 0), (1, 1), 0.5),
+    (1, 1, 9, 7, 3, 2, (3, 2), (1, 1), (2, 3), 1.0),
+    (3, 1, 4, 4, 1, 1, (1, 1), (0, 0), (1, 1), 0.6),
+    (1, 2, 6, 6, 4, 4, (1, 1), (3, 3), (1, 1), 0.8),
+    (3, 16, 17, 19, 5, 5, (2, 2), (2, 2), (1, 1), 0.3),      # 400 candidates per row: several wave passes
+    (4, 8, 12, 10, 3, 3, (1, 2), (2, 1), (2, 1), 0.5),
+    (2, 40, 6, 6, 3, 3, (1, 1), (0, 0), (1, 1), 0.0),        # everything pruned: an empty matrix
+]
+
+
+@pytest.mark.parametrize("ci,co,h,w,kh,kw,stride,padding,dilation,keep", CONV_GEOMETRIES)
+def test_generic_conv_builder_bit_exact(bp, ci, co, h, w, kh, kw, stride, padding, dilation, keep):
+    """bppsa_csr_conv2d_* against the oracle's entry-by-entry Jacobian: row pointers, column indices
+    and values, all bit-exact (no entry is a sum)."""
+    rng = np.random.default_rng(ci * 100 + co * 10 + kh)
+    wt = rng.standard_normal((co, ci, kh, kw)).astype(np.float32)
+    mask = rng.random(wt.shape) < keep
+    ref = ocnn.conv2d_jacobian_T(wt, mask, h, w, stride, padding, dilation)
+    got = bp.csr_conv2d(to_gpu(wt), to_gpu(mask.astype(np.uint8)), h, w, stride, padding, dilation)
+    assert (got.rows, got.cols) == ref.shape
+    _assert_same_csr(got, ref)
+
+
+def test_generic_conv_builder_equals_the_3x3_builder(bp):
+    import torch
+    rng = np.random.default_rng(77)
+    wt = to_gpu(rng.standard_normal((64, 3, 3, 3)).astype(np.float32))
+    mask = to_gpu((rng.random((64, 3, 3, 3)) < 0.4).astype(np.uint8))
+    a = bp.csr_conv3x3(wt, mask, 32, 32)
+    b = bp.csr_conv2d(wt, mask, 32, 32, (1, 1), (1, 1), (1, 1))
+    assert torch.equal(a.indptr, b.indptr) and torch.equal(a.indices, b.indices) and torch.equal(a.data, b.data)
+    full = bp.csr_conv2d(wt, None, 32, 32, (1, 1), (1, 1), (1, 1))
+    assert full.nnz == 1696512                                 # Table 1's first convolution of VGG-11
+
+
+def test_spscan_through_strided_and_dilated_convolutions(bp):
+    """A chain conv(5x5, stride 2) -> ReLU -> conv(3x3, dilation 2) -> ReLU -> fc: the sparse scan
+    over the generic builder's Jacobians against the oracle's matrix-vector chain on its own."""
+    import torch
+    rng = np.random.default_rng(12)
+    w1 = rng.standard_normal((4, 2, 5, 5)).astype(np.float32)
+    w2 = rng.standard_normal((3, 4, 3, 3)).astype(np.float32)
+    m1, m2 = rng.random(w1.shape) < 0.6, rng.random(w2.shape) < 0.6
+    h0 = w0 = 15
+    h1 = ocnn.conv2d_out_size(h0, 5, 2, 2, 1)                 # 8
+    h2 = ocnn.conv2d_out_size(h1, 3, 1, 2, 2)                 # 8
+    wf = rng.standard_normal((5, 3 * h2 * h2)).astype(np.float32)
+    mf = rng.random(wf.shape) < 0.5
+    a1 = rng.standard_normal(4 * h1 * h1).astype(np.float32)
+    a2 = rng.standard_normal(3 * h2 * h2).astype(np.float32)
+    ref = [ocnn.fc_jacobian_T(wf, mf), ocnn.relu_jacobian_T(a2),
+           ocnn.conv2d_jacobian_T(w2, m2, h1, h1, (1, 1), (2, 2), (2, 2)), ocnn.relu_jacobian_T(a1),
+           ocnn.conv2d_jacobian_T(w1, m1, h0, w0, (2, 2), (2, 2), (1, 1))]
+    jts = [bp.csr_linear(to_gpu(wf), to_gpu(mf.astype(np.uint8))), bp.csr_relu(to_gpu(a2)),
+           bp.csr_conv2d(to_gpu(w2), to_gpu(m2.astype(np.uint8)), h1, h1, (1, 1), (2, 2), (2, 2)),
+           bp.csr_relu(to_gpu(a1)),
+           bp.csr_conv2d(to_gpu(w1), to_gpu(m1.astype(np.uint8)), h0, w0, (2, 2), (2, 2), (1, 1))]
+    for g, r in zip(jts, ref):
+        _assert_same_csr(g, r)
+    seed = rng.standard_normal(5).astype(np.float32)
+    want = ocnn.sparse_linear_scan(ref, seed)
+    for U in (0, 1, 2):
+        arena = torch.empty((1 << 26,), dtype=torch.uint8, device="cuda")
+        plan = bp.SpscanPlan(jts, U, arena)
+        grads = [torch.empty((m.rows,), dtype=torch.float32, device="cuda") for m in jts]
+        plan.run(jts, to_gpu(seed), grads)
+        torch.cuda.synchronize()
+        for k in range(len(jts)):
+            assert rel_err(to_np(grads[k]), want[k]) <= TOL, (U, k)
+        plan.close()

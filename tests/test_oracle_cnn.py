@@ -83,6 +83,56 @@ def test_conv_jacobian_matches_unit_impulses(ci, co, h, w):
     assert all(np.all(np.diff(jt.indices[jt.indptr[r]:jt.indptr[r + 1]]) > 0) for r in range(jt.shape[0]))
 
 
+GEOMETRIES = [  # (ci, co, h, w, kh, kw, stride, padding, dilation)
+    (2, 3, 5, 6, 3, 3, (1, 1), (1, 1), (1, 1)),
+    (1, 2, 7, 5, 5, 3, (2, 1), (2, 0), (1, 1)),
+    (2, 2, 8, 8, 2, 2, (2, 2), (0, 0), (1, 1)),
+    (1, 1, 9, 7, 3, 2, (3, 2), (1, 1), (2, 3)),
+    (3, 1, 4, 4, 1, 1, (1, 1), (0, 0), (1, 1)),
+    (1, 2, 6, 6, 4, 4, (1, 1), (3, 3), (1, 1)),
+    (2, 1, 5, 5, 7, 7, (1, 1), (0, 0), (1, 1)),     # kernel larger than the image: no output
+]
+
+
+@pytest.mark.parametrize("ci,co,h,w,kh,kw,stride,padding,dilation", GEOMETRIES)
+def test_generic_conv_and_its_jacobian(ci, co, h, w, kh, kw, stride, padding, dilation):
+    from scipy.signal import correlate2d
+    rng = np.random.default_rng(kh * 10 + kw)
+    wt = rng.standard_normal((co, ci, kh, kw))
+    mask = rng.random((co, ci, kh, kw)) < 0.7
+    wm = np.where(mask, wt, 0.0)
+    x = rng.standard_normal((ci, h, w))
+    out = cnn.conv2d(x, wm, stride, padding, dilation)
+    oh, ow = cnn.conv2d_out_size(h, kh, stride[0], padding[0], dilation[0]), \
+        cnn.conv2d_out_size(w, kw, stride[1], padding[1], dilation[1])
+    assert out.shape == (co, oh, ow)
+    if dilation == (1, 1) and oh > 0 and ow > 0:
+        # SciPy's full-padded correlation, cropped to this padding and sampled at this stride
+        xp = np.pad(x, ((0, 0), (padding[0],) * 2, (padding[1],) * 2))
+        ref = np.stack([sum(correlate2d(xp[c], wm[o, c], mode="valid") for c in range(ci)) for o in range(co)])
+        assert np.allclose(out, ref[:, ::stride[0], ::stride[1]], rtol=1e-12, atol=1e-12)
+    jt = cnn.conv2d_jacobian_T(wm, mask, h, w, stride, padding, dilation)
+    assert jt.shape == (ci * h * w, co * oh * ow)
+    dense = _impulse_jacobian_T(lambda e: cnn.conv2d(e.reshape(ci, h, w), wm, stride, padding, dilation), ci * h * w)
+    assert np.array_equal(jt.toarray(), dense.reshape(ci * h * w, co * oh * ow))
+    pat = _impulse_jacobian_T(lambda e: cnn.conv2d(e.reshape(ci, h, w), mask.astype(float), stride, padding, dilation),
+                              ci * h * w).reshape(ci * h * w, -1)
+    got_pat = sp.csr_matrix((np.ones(jt.nnz), jt.indices, jt.indptr), shape=jt.shape).toarray()
+    assert np.array_equal(got_pat != 0, pat != 0)
+    assert all(np.all(np.diff(jt.indices[jt.indptr[r]:jt.indptr[r + 1]]) > 0) for r in range(jt.shape[0]))
+
+
+def test_generic_conv_reduces_to_the_3x3_case():
+    rng = np.random.default_rng(9)
+    wt = rng.standard_normal((4, 3, 3, 3))
+    mask = rng.random(wt.shape) < 0.5
+    x = rng.standard_normal((3, 6, 5))
+    assert np.allclose(cnn.conv2d(x, wt, (1, 1), (1, 1)), cnn.conv3x3(x, wt), rtol=1e-13, atol=1e-13)
+    a = cnn.conv2d_jacobian_T(wt, mask, 6, 5, (1, 1), (1, 1))
+    b = cnn.conv_jacobian_T(wt, mask, 6, 5)
+    assert np.array_equal(a.indptr, b.indptr) and np.array_equal(a.indices, b.indices) and np.array_equal(a.data, b.data)
+
+
 def test_kept_zero_weight_stays_structural():
     w = np.zeros((1, 1, 3, 3))
     jt = cnn.conv_jacobian_T(w, np.ones((1, 1, 3, 3), bool), 2, 2)
