@@ -282,7 +282,23 @@ def gru_workload(bp, workloads, steps):
     mm = (nseg - 2) * (S - 1) * B
     flop = mm * 2 * H ** 3 + T * B * 2 * H * H
     tf = flop / (parts["scan_ms"] * 1e-3) / 1e12
+    # the same backward pass with the Jacobians generated inside the scan (no Jt array)
+    del Jt
+    torch.cuda.empty_cache()
+    fws = torch.empty(bp.gru_scan_fused_workspace_bytes(T, B, H), dtype=torch.uint8, device="cuda")
+    fused = lambda: bp.gru_scan_fused(h, d["x"], d["w_ih"], d["w_hh"], d["b_ih"], d["b_hh"], seed, G=G, workspace=fws)
+    fused()
+    torch.cuda.synchronize()
+    fev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    for a, z in fev:
+        a.record()
+        fused()
+        z.record()
+    torch.cuda.synchronize()
+    fused_ms = statistics.mean(a.elapsed_time(z) for a, z in fev)
     return {"workload": "gru_H128_I1_T4096_B16 (configs[3])", **{k: round(v, 4) for k, v in parts.items()},
+            "fused_scan_ms": round(fused_ms, 4),
+            "fused_vs_build_plus_scan": round((parts["build_jacobians_ms"] + parts["scan_ms"]) / fused_ms, 3),
             "scan_matrix_products": mm, "scan_flop": flop, "scan_tflops": round(tf, 2),
             "frac_of_fp32_mfma_peak": round(tf / 157.3, 4),
             "scan_bytes_min": T * B * (4 * H * H + 4 * H), "jacobian_bytes": 4 * T * B * H * H}
@@ -610,7 +626,7 @@ def main():
         torch.cuda.empty_cache()
         g = gru_workload(bp, workloads, 5)
         out["gru"] = {k: g[k] for k in ("workload", "build_jacobians_ms", "scan_ms", "param_grads_ms",
-                                        "scan_tflops", "frac_of_fp32_mfma_peak")}
+                                        "fused_scan_ms", "scan_tflops", "frac_of_fp32_mfma_peak")}
         torch.cuda.empty_cache()
         c = cnn_workload(bp, workloads, 10)
         out["cnn"] = {"workload": c["workload"], "nnz": c["nnz"], "build_all_jacobians_ms": c["build_all_jacobians_ms"],

@@ -163,6 +163,24 @@ bppsa_status bppsa_rnn_scan_fused(int T, int B, int H, const float* h, const flo
                                   const float* seed, float* G, float* g0,
                                   void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * The GRU counterpart for H = 128 (the size of Section 4.2's workload): the scan with the
+ * transposed Jacobians of Appendix E's closed form generated inside its kernels from the
+ * hidden states, the inputs and the weights, so no [T,B,H,H] array exists.  A first kernel
+ * recomputes the gates of every step and keeps four H-vectors per step; the kernels of the scan
+ * then form each Jacobian from those and the three recurrent matrices held in registers.
+ * Arguments as for bppsa_build_jacobians (cell GRU) followed by bppsa_scan; the result equals
+ * those two calls up to rounding.  workspace: at least bppsa_gru_scan_fused_workspace_bytes
+ * bytes (0 for sizes it does not serve), 256-byte aligned.  Other H: BPPSA_EUNSUPPORTED.
+ */
+size_t bppsa_gru_scan_fused_workspace_bytes(int T, int B, int H);
+bppsa_status bppsa_gru_scan_fused(int T, int B, int H, int I,
+                                  const float* h, const float* x,
+                                  const float* w_ih, const float* w_hh,
+                                  const float* b_ih, const float* b_hh,
+                                  const float* seed, float* G, float* g0,
+                                  void* workspace, size_t workspace_bytes, void* stream);
+
 /* Bytes of workspace bppsa_param_grads needs (host-only, pure). */
 size_t bppsa_param_grads_workspace_bytes(int cell, int T, int B, int H, int I);
 

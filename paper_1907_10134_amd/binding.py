@@ -89,6 +89,10 @@ def _load(path=_LIB_PATH):
     lib.bppsa_spscan_plan_flops.argtypes = [c_void_p, ctypes.POINTER(ctypes.c_int64),
                                             ctypes.POINTER(ctypes.c_int64)]
     c_double = ctypes.c_double
+    lib.bppsa_gru_scan_fused_workspace_bytes.restype = c_size_t
+    lib.bppsa_gru_scan_fused_workspace_bytes.argtypes = [c_int] * 3
+    lib.bppsa_gru_scan_fused.restype = c_int
+    lib.bppsa_gru_scan_fused.argtypes = [c_int] * 4 + [c_void_p] * 10 + [c_size_t, c_void_p]
     lib.bppsa_head_backward.restype = c_int
     lib.bppsa_head_backward.argtypes = [c_int] * 3 + [c_void_p] * 8 + [c_void_p]
     lib.bppsa_adam_step.restype = c_int
@@ -275,6 +279,26 @@ def rnn_scan_fused(h, w_hh, seed, G=None, g0=None, workspace=None, stream=None):
                                      _ptr(G, name="G"), _ptr(g0),
                                      workspace.data_ptr(), workspace.numel(), _stream(stream)),
            "bppsa_rnn_scan_fused")
+    return G
+
+
+def gru_scan_fused_workspace_bytes(T, B, H):
+    return int(_lib.bppsa_gru_scan_fused_workspace_bytes(T, B, H))
+
+
+def gru_scan_fused(h, x, w_ih, w_hh, b_ih, b_hh, seed, G=None, g0=None, workspace=None, stream=None):
+    """bppsa_gru_scan_fused: the H = 128 GRU scan with the Jacobians generated inside its kernels."""
+    T1, B, H = h.shape
+    T = T1 - 1
+    I = x.shape[2]
+    if G is None:
+        G = torch.empty((T, B, H), dtype=torch.float32, device=h.device)
+    if workspace is None:
+        workspace = _workspace(gru_scan_fused_workspace_bytes(T, B, H), h.device)
+    _check(_lib.bppsa_gru_scan_fused(T, B, H, I, _ptr(h, name="h"), _ptr(x, name="x"), _ptr(w_ih), _ptr(w_hh),
+                                     _ptr(b_ih), _ptr(b_hh), _ptr(seed, name="seed"), _ptr(G, name="G"), _ptr(g0),
+                                     workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                                     _stream(stream)), "bppsa_gru_scan_fused")
     return G
 
 

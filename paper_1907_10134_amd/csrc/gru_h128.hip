@@ -2,6 +2,7 @@
 // run on the matrix cores; the Jacobians (Appendix E) are then streamed out with the three
 // recurrent weight matrices held in registers.
 #include "bppsa_internal.h"
+#include "scan_plan.h"
 
 namespace {
 
@@ -150,6 +151,39 @@ gru_jacobians_h128_kernel(long long rows, int I, long long nbatch, const float* 
   }
 }
 
+// The coefficient vectors of the closed form above for every (t, b) row, coef[row][4][H] =
+// (a, c, e, z), for a scan that generates the Jacobians itself instead of reading them.
+__global__ void __launch_bounds__(256)
+gru_coefs_h128_kernel(long long rows, int I, const float* __restrict__ h, const float* __restrict__ x,
+                      const float* __restrict__ w_ih, const float* __restrict__ w_hh,
+                      const float* __restrict__ b_ih, const float* __restrict__ b_hh, float* __restrict__ coef) {
+  __shared__ __attribute__((aligned(16))) float hp[kBatch * LS];
+  const int tid = threadIdx.x;
+  const long long row0 = (long long)blockIdx.x * kBatch;
+  stage_hidden<256>(tid, row0, rows, h, hp);
+  __syncthreads();
+  gru_gates_h128(tid >> 6, tid & 63, row0, rows, I, hp, x, w_ih, w_hh, b_ih, b_hh,
+                 [&](int row, int j, float r, float z, float n, float M, float hprev) {
+                   const float dn = (1.f - z) * (1.f - n * n);
+                   float* c = coef + (size_t)(row0 + row) * 4 * H;
+                   c[j] = dn * M * r * (1.f - r);
+                   c[H + j] = dn * r;
+                   c[2 * H + j] = (hprev - n) * z * (1.f - z);
+                   c[3 * H + j] = z;
+                 });
+}
+
+// wT[g][i][j] = W_hg[j][i] for g = r, n, z (the order of the coefficients a, c, e)
+__global__ void __launch_bounds__(256)
+gru_transpose_weights_h128_kernel(const float* __restrict__ w_hh, float* __restrict__ wT) {
+  const int e = blockIdx.x * blockDim.x + threadIdx.x;      // over 3 * H * H
+  if (e >= 3 * H * H) return;
+  const int g = e / (H * H), rem = e - g * H * H;
+  const int i = rem / H, j = rem - i * H;
+  const int src_gate = g == 0 ? 0 : (g == 1 ? 2 : 1);       // w_hh rows are ordered r, z, n
+  wT[e] = w_hh[((size_t)src_gate * H + j) * H + i];
+}
+
 // delta[row][0..4H) = (dR, dZ, dN, dM) for every (t, b) row, given g = dL/dh[t+1]: the chain
 // rule through the cell of Section 4.2 with the gates recomputed as above.
 constexpr int kDeltaThreads = 256;
@@ -275,6 +309,18 @@ bppsa_status bppsa_build_jacobians_gru_h128(int T, int B, int I, const float* h,
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
   gru_jacobians_h128_kernel<<<(int)grid, kJacThreads, lds, stream>>>(rows, I, nbatch, h, x, w_ih, w_hh, b_ih,
                                                                     b_hh, Jt);
+  BPPSA_CHECK_LAUNCH();
+  return BPPSA_OK;
+}
+
+bppsa_status bppsa_gru_coefs_h128(long long rows, int I, const float* h, const float* x, const float* w_ih,
+                                  const float* w_hh, const float* b_ih, const float* b_hh, float* coef,
+                                  float* wT, hipStream_t stream) {
+  const long long nbatch = (rows + kBatch - 1) / kBatch;
+  if (nbatch > 0x7fffffffLL) return BPPSA_EOVERFLOW;
+  gru_transpose_weights_h128_kernel<<<3 * H * H / 256, 256, 0, stream>>>(w_hh, wT);
+  BPPSA_CHECK_LAUNCH();
+  gru_coefs_h128_kernel<<<(int)nbatch, 256, 0, stream>>>(rows, I, h, x, w_ih, w_hh, b_ih, b_hh, coef);
   BPPSA_CHECK_LAUNCH();
   return BPPSA_OK;
 }

@@ -105,3 +105,36 @@ extern "C" bppsa_status bppsa_rnn_scan_fused(int T, int B, int H, const float* h
   if ((uintptr_t)workspace & 255) return BPPSA_EINVAL;
   return bppsa_scan_h20(T, B, nullptr, seed, G, g0, workspace, (hipStream_t)stream, h, w_hh);
 }
+
+// Layout of the fused GRU scan's workspace: coefficient vectors, transposed weights, then the
+// workspace of the scan itself.
+static size_t gru_fused_coef_bytes(int T, int B, int H) { return bppsa_align_up((size_t)T * B * 4 * H * sizeof(float), 256); }
+static size_t gru_fused_wt_bytes(int H) { return bppsa_align_up((size_t)3 * H * H * sizeof(float), 256); }
+
+extern "C" size_t bppsa_gru_scan_fused_workspace_bytes(int T, int B, int H) {
+  if (T < 1 || B < 1 || H != 128) return 0;
+  if (bppsa_mul_overflows(T, B, H, H)) return 0;
+  return gru_fused_coef_bytes(T, B, H) + gru_fused_wt_bytes(H) + scan_ws_bytes(T, B, H);
+}
+
+extern "C" bppsa_status bppsa_gru_scan_fused(int T, int B, int H, int I, const float* h, const float* x,
+                                             const float* w_ih, const float* w_hh, const float* b_ih,
+                                             const float* b_hh, const float* seed, float* G, float* g0,
+                                             void* workspace, size_t workspace_bytes, void* stream) {
+  if (T < 1 || B < 1 || H < 1 || I < 1) return BPPSA_EINVAL;
+  if (!h || !x || !w_ih || !w_hh || !seed || !G) return BPPSA_EINVAL;
+  if (bppsa_mul_overflows(T, B, H, H)) return BPPSA_EOVERFLOW;
+  if (B > 65535) return BPPSA_ESHAPE;
+  if (H != 128) return BPPSA_EUNSUPPORTED;       // the generating kernels exist for this size only
+  const size_t need = bppsa_gru_scan_fused_workspace_bytes(T, B, H);
+  if (!workspace || workspace_bytes < need) return BPPSA_EWORKSPACE;
+  if ((uintptr_t)workspace & 255) return BPPSA_EINVAL;
+  char* ws = static_cast<char*>(workspace);
+  float* coef = reinterpret_cast<float*>(ws);
+  float* wT = reinterpret_cast<float*>(ws + gru_fused_coef_bytes(T, B, H));
+  void* scan_ws = ws + gru_fused_coef_bytes(T, B, H) + gru_fused_wt_bytes(H);
+  hipStream_t s = (hipStream_t)stream;
+  BPPSA_TRY(bppsa_gru_coefs_h128((long long)T * B, I, h, x, w_ih, w_hh, b_ih, b_hh, coef, wT, s));
+  const bppsa_gru_tiles gen{coef, wT};
+  return bppsa_scan_generic(T, B, H, nullptr, seed, G, g0, scan_ws, s, &gen);
+}

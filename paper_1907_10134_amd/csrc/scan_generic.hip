@@ -132,10 +132,12 @@ int lanes_per_row(int H) {
   return lpr;
 }
 
+// gen (H = 128 only): the matrices of this level are generated instead of read from Jt
 bppsa_status launch_reduce(int T, int B, int H, int t_min, int S, int seg_begin, int seg_count,
-                           const float* Jt, float* tot, hipStream_t s) {
+                           const float* Jt, float* tot, hipStream_t s, const bppsa_gru_tiles* gen = nullptr) {
   if (seg_count <= 0) return BPPSA_OK;
-  if (H == 128) return bppsa_reduce_h128(T, B, t_min, S, seg_begin, seg_count, Jt, tot, s);
+  if (H == 128) return bppsa_reduce_h128(T, B, t_min, S, seg_begin, seg_count, Jt, tot, s, gen);
+  if (gen) return BPPSA_EUNSUPPORTED;
   const size_t lds = (size_t)2 * H * H * sizeof(float);
   dim3 grid(seg_count, B);
   const int HH = H * H;
@@ -157,10 +159,11 @@ bppsa_status launch_reduce(int T, int B, int H, int t_min, int S, int seg_begin,
 
 bppsa_status launch_apply(int T, int B, int H, int t_min, int S, int seg_begin, int seg_count,
                           const float* Jt, const float* vin, int vin_is_seed,
-                          float* G, float* g0, float* v_out, hipStream_t s) {
+                          float* G, float* g0, float* v_out, hipStream_t s, const bppsa_gru_tiles* gen = nullptr) {
   if (seg_count <= 0) return BPPSA_OK;
   if (H == 128)
-    return bppsa_apply_h128(T, B, t_min, S, seg_begin, seg_count, Jt, vin, vin_is_seed, G, g0, v_out, s);
+    return bppsa_apply_h128(T, B, t_min, S, seg_begin, seg_count, Jt, vin, vin_is_seed, G, g0, v_out, s, gen);
+  if (gen) return BPPSA_EUNSUPPORTED;
   dim3 grid(seg_count, B);
   apply_segments_kernel<<<grid, kThreads, (size_t)2 * H * sizeof(float), s>>>(
       T, B, H, t_min, S, seg_begin, lanes_per_row(H), Jt, vin, vin_is_seed, G, g0, v_out);
@@ -208,7 +211,7 @@ SideStream* side_stream() {
 // on a compute unit (188 + 148 registers per lane, 135 KB + 1 KB of LDS).
 bppsa_status scan_h128_pipelined(int T, int B, int t_min, int S, int nseg, const float* Jt, const float* seed,
                                  float* G, float* g0, float* tot, float* vin, hipStream_t s, SideStream* side,
-                                 int slab) {
+                                 int slab, const bppsa_gru_tiles* gen) {
   constexpr int H = 128;
   const size_t row = (size_t)B * H;
   std::lock_guard<std::mutex> hold(side->lock);
@@ -221,7 +224,7 @@ bppsa_status scan_h128_pipelined(int T, int B, int t_min, int S, int nseg, const
   bppsa_status st = [&]() -> bppsa_status {
     // seed-side segment: matrix-vector only; its last vector enters segment nseg-2
     bppsa_status e = launch_apply(T, B, H, t_min, S, nseg - 1, 1, Jt, seed, 1, G, g0,
-                                  vin + (size_t)(nseg - 2) * row, s2);
+                                  vin + (size_t)(nseg - 2) * row, s2, gen);
     if (e != BPPSA_OK) return e;
     int j = 0;
     for (int hi = nseg - 2; hi >= 0; ++j) {
@@ -229,7 +232,7 @@ bppsa_status scan_h128_pipelined(int T, int B, int t_min, int S, int nseg, const
       if (lo <= 1) lo = 0;                        // segment 0 has no total: it rides with the last slab
       const int rlo = lo < 1 ? 1 : lo;            // totals exist for segments 1 .. nseg-2
       if (hi >= rlo) {
-        e = launch_reduce(T, B, H, t_min, S, rlo, hi - rlo + 1, Jt, tot, s);
+        e = launch_reduce(T, B, H, t_min, S, rlo, hi - rlo + 1, Jt, tot, s, gen);
         if (e != BPPSA_OK) return e;
       }
       BPPSA_HIP_TRY(hipEventRecord(side->slab[j], s));
@@ -241,7 +244,7 @@ bppsa_status scan_h128_pipelined(int T, int B, int t_min, int S, int nseg, const
                          nullptr, s2);
         if (e != BPPSA_OK) return e;
       }
-      e = launch_apply(T, B, H, t_min, S, lo, hi - lo + 1, Jt, vin, 0, G, g0, nullptr, s2);
+      e = launch_apply(T, B, H, t_min, S, lo, hi - lo + 1, Jt, vin, 0, G, g0, nullptr, s2, gen);
       if (e != BPPSA_OK) return e;
       hi = lo - 1;
     }
@@ -255,7 +258,7 @@ bppsa_status scan_h128_pipelined(int T, int B, int t_min, int S, int nseg, const
 
 // One level of the recursion; `ws` is the unused tail of the workspace.
 bppsa_status scan_level(int T, int B, int H, const float* Jt, const float* seed,
-                        float* G, float* g0, char* ws, hipStream_t s) {
+                        float* G, float* g0, char* ws, hipStream_t s, const bppsa_gru_tiles* gen = nullptr) {
   const size_t row = (size_t)B * H;
   if (seed != G + (size_t)(T - 1) * row) {
     const long long n = (long long)row;
@@ -266,7 +269,7 @@ bppsa_status scan_level(int T, int B, int H, const float* Jt, const float* seed,
   const int n = T - t_min;
   if (n <= 0) return BPPSA_OK;
   const int S = bppsa_generic_segment(H);
-  if (n <= S) return launch_apply(T, B, H, t_min, n, 0, 1, Jt, seed, 1, G, g0, nullptr, s);
+  if (n <= S) return launch_apply(T, B, H, t_min, n, 0, 1, Jt, seed, 1, G, g0, nullptr, s, gen);
 
   const int nseg = bppsa_ceil_div(n, S);
   const int T2 = nseg - 1;                               // length of the chain of totals
@@ -281,23 +284,25 @@ bppsa_status scan_level(int T, int B, int H, const float* Jt, const float* seed,
     if (slab < 1) slab = 1;
     if (bppsa_ceil_div(nseg - 1, slab) > kMaxSlabs) slab = bppsa_ceil_div(nseg - 1, kMaxSlabs);
     SideStream* side = (nseg - 2 >= 2 * slab) ? side_stream() : nullptr;
-    if (side) return scan_h128_pipelined(T, B, t_min, S, nseg, Jt, seed, G, g0, tot, vin, s, side, slab);
+    if (side) return scan_h128_pipelined(T, B, t_min, S, nseg, Jt, seed, G, g0, tot, vin, s, side, slab, gen);
   }
   // interior segments 1..nseg-2: matrix-matrix totals (segment 0's total reaches no output)
-  st = launch_reduce(T, B, H, t_min, S, 1, nseg - 2, Jt, tot, s);
+  st = launch_reduce(T, B, H, t_min, S, 1, nseg - 2, Jt, tot, s, gen);
   if (st != BPPSA_OK) return st;
   // seed-side segment: matrix-vector only; its last vector seeds the chain of totals
-  st = launch_apply(T, B, H, t_min, S, nseg - 1, 1, Jt, seed, 1, G, g0, vin + (size_t)(T2 - 1) * row, s);
+  st = launch_apply(T, B, H, t_min, S, nseg - 1, 1, Jt, seed, 1, G, g0, vin + (size_t)(T2 - 1) * row, s, gen);
   if (st != BPPSA_OK) return st;
   // incoming vectors of segments 0..nseg-2 = scan over the totals
   st = scan_level(T2, B, H, tot, vin + (size_t)(T2 - 1) * row, vin, nullptr, ws, s);
   if (st != BPPSA_OK) return st;
-  return launch_apply(T, B, H, t_min, S, 0, nseg - 1, Jt, vin, 0, G, g0, nullptr, s);
+  return launch_apply(T, B, H, t_min, S, 0, nseg - 1, Jt, vin, 0, G, g0, nullptr, s, gen);
 }
 
 }  // namespace
 
 bppsa_status bppsa_scan_generic(int T, int B, int H, const float* Jt, const float* seed,
-                                float* G, float* g0, void* workspace, hipStream_t stream) {
-  return scan_level(T, B, H, Jt, seed, G, g0, static_cast<char*>(workspace), stream);
+                                float* G, float* g0, void* workspace, hipStream_t stream,
+                                const bppsa_gru_tiles* gen) {
+  if (gen && H != 128) return BPPSA_EUNSUPPORTED;
+  return scan_level(T, B, H, Jt, seed, G, g0, static_cast<char*>(workspace), stream, gen);
 }

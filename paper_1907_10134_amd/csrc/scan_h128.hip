@@ -26,6 +26,42 @@ __device__ __forceinline__ void seg_bounds(int T, int t_min, int S, int seg, int
   hi = min(lo + S, T) - 1;
 }
 
+// GRU transposed Jacobians generated in place of being read (Appendix E):
+//   Jt[i][j] = W_hr[j][i] a_j + W_hn[j][i] c_j + W_hz[j][i] e_j + [i == j] z_j
+// with the per-step coefficient vectors (a, c, e, z) of bppsa_gru_coefs_h128 and the three
+// recurrent matrices transposed, wT[g][i][j] (g = r, n, z).  Both kernels below give thread tid
+// the 16-byte pieces e = tid + 256 q of a tile, i.e. rows tid / 32 + 8 q and columns
+// 4 (tid % 32) .. + 3: the same places in every tile, so the thread keeps its 3 x 16 pieces of
+// the weights in registers for the whole segment and a tile costs it four coefficient reads and
+// 192 multiply-adds instead of 256 bytes from HBM.
+struct GruWeights {
+  v4f r[kChunks], n[kChunks], z[kChunks];
+};
+struct GruCoef {
+  v4f a, c, e, z;
+};
+
+__device__ __forceinline__ void load_gru_weights(const float* __restrict__ wT, int tid, GruWeights& w) {
+#pragma unroll
+  for (int q = 0; q < kChunks; ++q) {
+    const int e = tid + q * kThreads;
+    w.r[q] = reinterpret_cast<const v4f*>(wT)[e];
+    w.n[q] = reinterpret_cast<const v4f*>(wT + HH)[e];
+    w.z[q] = reinterpret_cast<const v4f*>(wT + 2 * HH)[e];
+  }
+}
+__device__ __forceinline__ GruCoef load_gru_coef(const float* __restrict__ coef, size_t row, int tid) {
+  const v4f* c = reinterpret_cast<const v4f*>(coef + row * 4 * H) + (tid & 31);
+  return GruCoef{c[0], c[H / 4], c[2 * (H / 4)], c[3 * (H / 4)]};
+}
+__device__ __forceinline__ v4f gru_piece(const GruWeights& w, const GruCoef& cf, int tid, int q) {
+  v4f o = w.r[q] * cf.a + w.n[q] * cf.c + w.z[q] * cf.e;
+  const int d = (tid >> 5) + 8 * q - 4 * (tid & 31);      // row minus first column of the piece
+#pragma unroll
+  for (int u = 0; u < 4; ++u) o[u] += (d == u) ? cf.z[u] : 0.f;
+  return o;
+}
+
 // P <- J P for J = Jt[hi-1], ..., Jt[lo], starting from P = Jt[hi]; tot[seg][b] = P.
 //
 // v_mfma_f32_32x32x2_f32 contracts two k values per issue: lane l supplies A[i = l % 32][k(l / 32)]
@@ -35,9 +71,11 @@ __device__ __forceinline__ void seg_bounds(int T, int t_min, int S, int seg, int
 // 16-byte LDS read per operand feeds four issues.  A is stored [i][k] and the running product
 // is stored transposed, [j][k], which is also the order in which the accumulators come out.
 // Each of the four waves owns a 64 x 64 quadrant of the product (2 x 2 MFMA blocks).
+// GEN: the Jacobians are generated from (coef, wT) instead of read from Jt.
+template <bool GEN>
 __global__ void __launch_bounds__(kThreads, 1)
 reduce_h128_kernel(int T, int B, int t_min, int S, int seg_begin, const float* __restrict__ Jt,
-                   float* __restrict__ tot) {
+                   float* __restrict__ tot, const float* __restrict__ coef, const float* __restrict__ wT) {
   extern __shared__ __attribute__((aligned(16))) float smem[];
   float* As = smem;                 // [128][LS]  A[i][k]
   float* Bt = smem + H * LS;        // [128][LS]  P^T: Bt[j][k] = P[k][j]
@@ -50,14 +88,20 @@ reduce_h128_kernel(int T, int B, int t_min, int S, int seg_begin, const float* _
   int lo, hi;
   seg_bounds(T, t_min, S, seg, lo, hi);
 
+  GruWeights gw;
+  GruCoef cf;
+  if (GEN) {
+    load_gru_weights(wT, tid, gw);
+    cf = load_gru_coef(coef, (size_t)hi * B + b, tid);
+  }
   // P = Jt[hi], written transposed (once per segment)
   {
-    const float* src = Jt + ((size_t)hi * B + b) * HH;
-#pragma unroll 4
+    const float* src = GEN ? nullptr : Jt + ((size_t)hi * B + b) * HH;
+#pragma unroll
     for (int r = 0; r < kChunks; ++r) {
       const int e = tid + r * kThreads;
       const int k = e >> 5, j4 = (e & 31) * 4;
-      const v4f x = reinterpret_cast<const v4f*>(src)[e];
+      const v4f x = GEN ? gru_piece(gw, cf, tid, r) : reinterpret_cast<const v4f*>(src)[e];
       Bt[(j4 + 0) * LS + k] = x[0];
       Bt[(j4 + 1) * LS + k] = x[1];
       Bt[(j4 + 2) * LS + k] = x[2];
@@ -65,24 +109,32 @@ reduce_h128_kernel(int T, int B, int t_min, int S, int seg_begin, const float* _
     }
   }
   v16f acc[2][2];
-  v4f pre[kChunks];
+  v4f pre[GEN ? 1 : kChunks];
   if (hi - 1 >= lo) {
-    const float* src = Jt + ((size_t)(hi - 1) * B + b) * HH;
+    if (GEN) {
+      cf = load_gru_coef(coef, (size_t)(hi - 1) * B + b, tid);
+    } else {
+      const float* src = Jt + ((size_t)(hi - 1) * B + b) * HH;
 #pragma unroll
-    for (int r = 0; r < kChunks; ++r) pre[r] = reinterpret_cast<const v4f*>(src)[tid + r * kThreads];
+      for (int r = 0; r < kChunks; ++r) pre[r] = reinterpret_cast<const v4f*>(src)[tid + r * kThreads];
+    }
   }
   for (int t = hi - 1; t >= lo; --t) {
-    // the prefetched Jacobian becomes the A operand
+    // the prefetched (or generated) Jacobian becomes the A operand
 #pragma unroll
     for (int r = 0; r < kChunks; ++r) {
       const int e = tid + r * kThreads;
-      *reinterpret_cast<v4f*>(As + (e >> 5) * LS + (e & 31) * 4) = pre[r];
+      *reinterpret_cast<v4f*>(As + (e >> 5) * LS + (e & 31) * 4) = GEN ? gru_piece(gw, cf, tid, r) : pre[r];
     }
     __syncthreads();
     if (t - 1 >= lo) {
-      const float* src = Jt + ((size_t)(t - 1) * B + b) * HH;
+      if (GEN) {
+        cf = load_gru_coef(coef, (size_t)(t - 1) * B + b, tid);
+      } else {
+        const float* src = Jt + ((size_t)(t - 1) * B + b) * HH;
 #pragma unroll
-      for (int r = 0; r < kChunks; ++r) pre[r] = reinterpret_cast<const v4f*>(src)[tid + r * kThreads];
+        for (int r = 0; r < kChunks; ++r) pre[r] = reinterpret_cast<const v4f*>(src)[tid + r * kThreads];
+      }
     }
 #pragma unroll
     for (int bi = 0; bi < 2; ++bi)
@@ -150,10 +202,12 @@ reduce_h128_kernel(int T, int B, int t_min, int S, int seg_begin, const float* _
 // Thread (r, c) = (tid / 32, tid % 32) holds columns 4c..4c+3 of rows r, r+8, ..., r+120; the 32
 // threads of a row group keep their slice of v in registers and reduce their partial sums with
 // a halving exchange (16 + 8 + 4 + 2 + 1 shuffles instead of 5 per row).
+template <bool GEN>
 __global__ void __launch_bounds__(kThreads)
 apply_h128_kernel(int T, int B, int t_min, int S, int seg_begin, const float* __restrict__ Jt,
                   const float* __restrict__ vin, int vin_is_seed, float* __restrict__ G,
-                  float* __restrict__ g0, float* __restrict__ v_out) {
+                  float* __restrict__ g0, float* __restrict__ v_out, const float* __restrict__ coef,
+                  const float* __restrict__ wT) {
   __shared__ __attribute__((aligned(16))) float vs[2][H];
   // this kernel may share a compute unit with the matrix-core kernel of the pipelined form
   __builtin_amdgcn_s_setprio(3);
@@ -165,8 +219,13 @@ apply_h128_kernel(int T, int B, int t_min, int S, int seg_begin, const float* __
   seg_bounds(T, t_min, S, seg, lo, hi);
   const float* vsrc = vin_is_seed ? vin + (size_t)b * H : vin + ((size_t)seg * B + b) * H;
   if (tid < H) vs[0][tid] = vsrc[tid];
-  v4f pre[kChunks];
-  {
+  v4f pre[GEN ? 1 : kChunks];
+  GruWeights gw;
+  GruCoef cf;
+  if (GEN) {
+    load_gru_weights(wT, tid, gw);
+    cf = load_gru_coef(coef, (size_t)hi * B + b, tid);
+  } else {
     const float* src = Jt + ((size_t)hi * B + b) * HH;
 #pragma unroll
     for (int q = 0; q < kChunks; ++q) pre[q] = reinterpret_cast<const v4f*>(src)[tid + q * kThreads];
@@ -177,12 +236,18 @@ apply_h128_kernel(int T, int B, int t_min, int S, int seg_begin, const float* __
     const v4f x = *reinterpret_cast<const v4f*>(&vs[cur][4 * c]);
     float part[kChunks];
 #pragma unroll
-    for (int q = 0; q < kChunks; ++q)           // row r + 8 q
-      part[q] = (pre[q][0] * x[0] + pre[q][1] * x[1]) + (pre[q][2] * x[2] + pre[q][3] * x[3]);
+    for (int q = 0; q < kChunks; ++q) {         // row r + 8 q
+      const v4f m = GEN ? gru_piece(gw, cf, tid, q) : pre[q];
+      part[q] = (m[0] * x[0] + m[1] * x[1]) + (m[2] * x[2] + m[3] * x[3]);
+    }
     if (t - 1 >= lo) {
-      const float* src = Jt + ((size_t)(t - 1) * B + b) * HH;
+      if (GEN) {
+        cf = load_gru_coef(coef, (size_t)(t - 1) * B + b, tid);
+      } else {
+        const float* src = Jt + ((size_t)(t - 1) * B + b) * HH;
 #pragma unroll
-      for (int q = 0; q < kChunks; ++q) pre[q] = reinterpret_cast<const v4f*>(src)[tid + q * kThreads];
+        for (int q = 0; q < kChunks; ++q) pre[q] = reinterpret_cast<const v4f*>(src)[tid + q * kThreads];
+      }
     }
     // halving exchange over the 32 lanes of the row group: after the step with mask m a lane
     // keeps the rows whose index bit matches its own lane bit
@@ -219,24 +284,36 @@ apply_h128_kernel(int T, int B, int t_min, int S, int seg_begin, const float* __
 }  // namespace
 
 bppsa_status bppsa_reduce_h128(int T, int B, int t_min, int S, int seg_begin, int seg_count,
-                               const float* Jt, float* tot, hipStream_t s) {
+                               const float* Jt, float* tot, hipStream_t s, const bppsa_gru_tiles* gen) {
   if (seg_count <= 0) return BPPSA_OK;
   const size_t lds = (size_t)2 * H * LS * sizeof(float);
   // set on every call: the attribute belongs to the current device's copy of the kernel, and the
   // library keeps no per-process record of which devices it has run on
-  BPPSA_HIP_TRY(hipFuncSetAttribute((const void*)reduce_h128_kernel,
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-  reduce_h128_kernel<<<dim3(seg_count, B), kThreads, lds, s>>>(T, B, t_min, S, seg_begin, Jt, tot);
+  if (gen) {
+    BPPSA_HIP_TRY(hipFuncSetAttribute((const void*)reduce_h128_kernel<true>,
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    reduce_h128_kernel<true><<<dim3(seg_count, B), kThreads, lds, s>>>(T, B, t_min, S, seg_begin, nullptr, tot,
+                                                                       gen->coef, gen->wT);
+  } else {
+    BPPSA_HIP_TRY(hipFuncSetAttribute((const void*)reduce_h128_kernel<false>,
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    reduce_h128_kernel<false><<<dim3(seg_count, B), kThreads, lds, s>>>(T, B, t_min, S, seg_begin, Jt, tot,
+                                                                        nullptr, nullptr);
+  }
   BPPSA_CHECK_LAUNCH();
   return BPPSA_OK;
 }
 
 bppsa_status bppsa_apply_h128(int T, int B, int t_min, int S, int seg_begin, int seg_count,
                               const float* Jt, const float* vin, int vin_is_seed, float* G, float* g0,
-                              float* v_out, hipStream_t s) {
+                              float* v_out, hipStream_t s, const bppsa_gru_tiles* gen) {
   if (seg_count <= 0) return BPPSA_OK;
-  apply_h128_kernel<<<dim3(seg_count, B), kThreads, 0, s>>>(T, B, t_min, S, seg_begin, Jt, vin, vin_is_seed,
-                                                            G, g0, v_out);
+  if (gen)
+    apply_h128_kernel<true><<<dim3(seg_count, B), kThreads, 0, s>>>(T, B, t_min, S, seg_begin, nullptr, vin,
+                                                                    vin_is_seed, G, g0, v_out, gen->coef, gen->wT);
+  else
+    apply_h128_kernel<false><<<dim3(seg_count, B), kThreads, 0, s>>>(T, B, t_min, S, seg_begin, Jt, vin,
+                                                                     vin_is_seed, G, g0, v_out, nullptr, nullptr);
   BPPSA_CHECK_LAUNCH();
   return BPPSA_OK;
 }

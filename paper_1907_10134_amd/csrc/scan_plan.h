@@ -51,12 +51,26 @@ bppsa_status bppsa_scan_h20(int T, int B, const float* Jt, const float* seed, fl
 bppsa_status bppsa_scan_h20_hops(int T, int B, int want_g0, int unit_halves, const void* workspace,
                                  long long* out, hipStream_t stream);
 
+// GRU transposed Jacobians (H = 128) given by what generates them instead of as tiles: coef
+// [T*B][4][H] = the per-step vectors (a, c, e, z) of Appendix E's closed form, wT [3][H][H] =
+// W_hr^T, W_hn^T, W_hz^T.  With such a source the top level of the scan reads no Jt.
+struct bppsa_gru_tiles {
+  const float* coef;
+  const float* wT;
+};
+
 bppsa_status bppsa_scan_generic(int T, int B, int H, const float* Jt, const float* seed,
-                                float* G, float* g0, void* workspace, hipStream_t stream);
+                                float* G, float* g0, void* workspace, hipStream_t stream,
+                                const bppsa_gru_tiles* gen = nullptr);
 
 // ---- matrix-core kernels for H = 128 (used by the generic scan's reduce and apply steps) ----
 bppsa_status bppsa_reduce_h128(int T, int B, int t_min, int S, int seg_begin, int seg_count,
-                               const float* Jt, float* tot, hipStream_t s);
+                               const float* Jt, float* tot, hipStream_t s, const bppsa_gru_tiles* gen = nullptr);
 bppsa_status bppsa_apply_h128(int T, int B, int t_min, int S, int seg_begin, int seg_count,
                               const float* Jt, const float* vin, int vin_is_seed, float* G, float* g0,
-                              float* v_out, hipStream_t s);
+                              float* v_out, hipStream_t s, const bppsa_gru_tiles* gen = nullptr);
+
+// coef and wT of bppsa_gru_tiles from the hidden states, inputs and weights (gates recomputed).
+bppsa_status bppsa_gru_coefs_h128(long long rows, int I, const float* h, const float* x, const float* w_ih,
+                                  const float* w_hh, const float* b_ih, const float* b_hh, float* coef,
+                                  float* wT, hipStream_t stream);

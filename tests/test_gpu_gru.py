@@ -228,3 +228,59 @@ def test_h128_long_scan_from_two_host_threads(bp):
         G_ref, g0_ref = _oracle_scan_in_chunks(Jt, to_np(seeds[i]))
         assert rel_err(to_np(outs[i][0]), G_ref) <= TOL
         assert rel_err(to_np(outs[i][1]), g0_ref) <= TOL
+
+
+def _fused_vs_oracle(bp, w, want_g0=True):
+    import torch
+    d = _dev(w)
+    h = _gpu_forward(bp, w, d)
+    seed, _ = bp.head_seed(h[-1].contiguous(), d["w_out"], d["b_out"], d["labels"])
+    g0 = torch.empty((w["B"], w["H"]), dtype=torch.float32, device="cuda") if want_g0 else None
+    G = bp.gru_scan_fused(h, d["x"], d["w_ih"], d["w_hh"], d["b_ih"], d["b_hh"], seed, g0=g0)
+    torch.cuda.synchronize()
+    return h, seed, to_np(G), None if g0 is None else to_np(g0)
+
+
+@pytest.mark.parametrize("T,B,I", [(7, 5, 1), (64, 2, 3), (65, 3, 1), (70, 2, 1), (300, 3, 2), (1000, 2, 1), (129, 33, 1)])
+def test_gru_scan_fused_matches_oracle_chain(bp, T, B, I):
+    """bppsa_gru_scan_fused (Jacobians generated inside the scan's kernels) against the oracle's
+    matrix-free chain, every element; sizes cover one segment, a ragged last segment, the chain of
+    totals and the two-stream form."""
+    w = workloads.gru_inputs(T, B, 128, I, 11, seed=5 * T + B)
+    h, seed, G, g0 = _fused_vs_oracle(bp, w)
+    h_ref, G_ref, g0_ref, _ = _oracle(w)
+    assert rel_err(G, G_ref) <= TOL
+    assert per_step_err(G, G_ref) <= 50 * TOL
+    if np.max(np.abs(g0_ref)) > 1e-30:            # below that the gradient has left fp32's range
+        assert rel_err(g0, g0_ref) <= 5 * TOL
+    else:
+        assert np.max(np.abs(g0)) <= 1e-30
+    # and equal, up to rounding, to the two calls on the same hidden states
+    d = _dev(w)
+    Jt = bp.build_jacobians(bp.GRU, h, d["x"], d["w_ih"], d["w_hh"], d["b_ih"], d["b_hh"])
+    G2 = to_np(bp.scan(Jt, seed))
+    assert rel_err(G, G2) <= 1e-5
+
+
+def test_gru_scan_fused_config3_full_size(bp):
+    """configs[3] (H=128, T=4096, B=16) through the fused call, every element against the oracle."""
+    w = workloads.config_inputs(3)
+    h, seed, G, g0 = _fused_vs_oracle(bp, w)
+    h_ref, G_ref, g0_ref, _ = _oracle(w)
+    assert rel_err(G, G_ref) <= TOL
+    assert per_step_err(G, G_ref) <= 100 * TOL
+    if np.max(np.abs(g0_ref)) > 1e-30:
+        assert rel_err(g0, g0_ref) <= 5 * TOL
+
+
+def test_gru_scan_fused_rejects_other_sizes(bp):
+    import torch
+    w = workloads.gru_inputs(10, 2, 64, 1, 11, seed=1)
+    d = _dev(w)
+    h = _gpu_forward(bp, w, d)
+    seed = torch.zeros((2, 64), dtype=torch.float32, device="cuda")
+    assert bp.gru_scan_fused_workspace_bytes(10, 2, 64) == 0
+    with pytest.raises(bp.BppsaError) as e:
+        bp.gru_scan_fused(h, d["x"], d["w_ih"], d["w_hh"], d["b_ih"], d["b_hh"], seed,
+                          workspace=torch.empty((1 << 20,), dtype=torch.uint8, device="cuda"))
+    assert e.value.code == 6
