@@ -417,6 +417,7 @@ def train_workload(bp, workloads, T, B, reps, materialise=False):
         z.record()
     torch.cuda.synchronize()
     total = statistics.median(a.elapsed_time(z) for a, z in evs)
+    bp.check_scan(tr.workspace)
     assert math.isfinite(float(tr.loss.item()))
 
     # the same calls one by one, for the breakdown (forward pass / backward pass / the rest)
@@ -555,6 +556,7 @@ def main():
     T, B, H = w["T"], w["B"], w["H"]
     bufs = prepare(bp, w)
     wall_ms, parts = time_steps(bp, bufs, args.steps, args.warmup)
+    bp.check_scan(bufs["scan_ws"])      # the timed scans ended normally
 
     cold_ms = time_steps_cold(bp, bufs, max(5, min(30, args.steps)))
     fused_wall_ms, fused_scan_ms = (None, None) if args.no_fused else time_fused(bp, bufs, args.steps, args.warmup)

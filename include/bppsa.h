@@ -242,8 +242,10 @@ bppsa_status bppsa_adam_step(int64_t n, float* theta, const float* grad, float* 
  * x is [T,B,I], labels [B] int32.  st->h is [T+1,B,H] with h[0] the initial state (the caller
  * zeroes it once; rows 1..T are overwritten), st->G [T,B,H], st->seed [B,H], st->loss [1] (may be
  * NULL), st->Jt [T,B,H,H] or NULL, st->workspace of at least
- * bppsa_rnn_train_workspace_bytes(T, B, H, I) bytes, 256-byte aligned.  The struct is host memory,
- * its pointers device memory; nothing is allocated.  st->loss receives the loss before the update.
+ * bppsa_rnn_train_workspace_bytes(T, B, H, I) bytes, 256-byte aligned (the scan's part comes
+ * first, so for H = 20 its first word is the scan's error flag after the iteration, as described
+ * at bppsa_scan).  The struct is host memory, its pointers device memory; nothing is allocated.
+ * st->loss receives the loss before the update.
  */
 typedef struct bppsa_rnn_train_state {
   float* params;

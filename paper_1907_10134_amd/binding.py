@@ -19,9 +19,9 @@ _LIB_PATH = os.path.join(_PKG, "libbppsa.so")
 
 
 class BppsaError(RuntimeError):
-    def __init__(self, code, where):
+    def __init__(self, code, where, detail=None):
         self.code = code
-        super().__init__("%s failed: %s" % (where, _lib.bppsa_strerror(code).decode()))
+        super().__init__("%s failed: %s" % (where, detail or _lib.bppsa_strerror(code).decode()))
 
 
 def _load(path=_LIB_PATH):
@@ -183,9 +183,29 @@ def _check(code, where):
         raise BppsaError(code, where)
 
 
-def _workspace(nbytes, device):
-    # 256-byte aligned by the caching allocator (its blocks are 512-byte aligned)
-    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+def _workspace(nbytes, device, stream=None):
+    # 256-byte aligned by the caching allocator (its blocks are 512-byte aligned).  A workspace
+    # made here for a stream other than the current one is tied to that stream, so the allocator
+    # does not hand its memory out again while the call is still running there.
+    ws = torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+    if stream is not None and stream != torch.cuda.current_stream(device):
+        ws.record_stream(stream)
+    return ws
+
+
+_last_h20_workspace = None      # the workspace of the latest H = 20 scan that allocated its own
+
+
+def check_scan(workspace=None):
+    """Synchronise and read the error word of an H = 20 scan's workspace (its first 4 bytes): raises
+    BppsaError if a bounded wait inside the kernel expired, in which case G is invalid.  With no
+    argument, checks the workspace the latest scan()/rnn_scan_fused() call allocated for itself."""
+    ws = _last_h20_workspace if workspace is None else workspace
+    if ws is None:
+        return
+    torch.cuda.synchronize(ws.device)
+    if int(ws[:4].view(torch.int32).item()) != 0:
+        raise BppsaError(5, "bppsa_scan", "a bounded wait inside the H = 20 scan expired; G is invalid")
 
 
 def forward(cell, x, w_ih, w_hh, b_ih, b_hh, h, stream=None):
@@ -235,7 +255,10 @@ def scan(Jt, seed, G=None, g0=None, workspace=None, stream=None):
     if G is None:
         G = torch.empty((T, B, H), dtype=torch.float32, device=Jt.device)
     if workspace is None:
-        workspace = _workspace(scan_workspace_bytes(T, B, H), Jt.device)
+        workspace = _workspace(scan_workspace_bytes(T, B, H), Jt.device, stream)
+        if H == 20:
+            global _last_h20_workspace
+            _last_h20_workspace = workspace
     _check(_lib.bppsa_scan(T, B, H, _ptr(Jt), _ptr(seed), _ptr(G), _ptr(g0),
                            workspace.data_ptr(), workspace.numel() * workspace.element_size(),
                            _stream(stream)), "bppsa_scan")
@@ -274,7 +297,9 @@ def rnn_scan_fused(h, w_hh, seed, G=None, g0=None, workspace=None, stream=None):
     if G is None:
         G = torch.empty((T, B, H), dtype=torch.float32, device=h.device)
     if workspace is None:
-        workspace = _workspace(scan_workspace_bytes(T, B, H), h.device)
+        workspace = _workspace(scan_workspace_bytes(T, B, H), h.device, stream)
+        global _last_h20_workspace
+        _last_h20_workspace = workspace
     _check(_lib.bppsa_rnn_scan_fused(T, B, H, _ptr(h, name="h"), _ptr(w_hh, name="w_hh"), _ptr(seed, name="seed"),
                                      _ptr(G, name="G"), _ptr(g0),
                                      workspace.data_ptr(), workspace.numel(), _stream(stream)),

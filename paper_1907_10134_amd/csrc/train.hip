@@ -135,10 +135,12 @@ extern "C" size_t bppsa_rnn_param_count(int H, int I, int C) {
   return (size_t)H * I + (size_t)H * H + 2 * (size_t)H + (size_t)C * H + (size_t)C;
 }
 
+// The scan's part comes first and stays untouched by the later calls, so its error word (the
+// first four bytes, H = 20) can still be read after the iteration.
+static size_t train_scan_ws_bytes(int T, int B, int H) { return bppsa_align_up(bppsa_scan_workspace_bytes(T, B, H), 256); }
+
 extern "C" size_t bppsa_rnn_train_workspace_bytes(int T, int B, int H, int I) {
-  const size_t a = bppsa_scan_workspace_bytes(T, B, H);
-  const size_t b = bppsa_param_grads_workspace_bytes(BPPSA_RNN_TANH, T, B, H, I);
-  return a > b ? a : b;
+  return train_scan_ws_bytes(T, B, H) + bppsa_param_grads_workspace_bytes(BPPSA_RNN_TANH, T, B, H, I);
 }
 
 extern "C" bppsa_status bppsa_rnn_train_step(int T, int B, int H, int I, int C, const float* x,
@@ -154,6 +156,9 @@ extern "C" bppsa_status bppsa_rnn_train_step(int T, int B, int H, int I, int C, 
                o_bout = o_wout + (size_t)C * H;
   const float* p = st->params;
   float* g = st->grads;
+  const size_t scan_bytes = train_scan_ws_bytes(T, B, H);
+  void* pg_ws = static_cast<char*>(st->workspace) + scan_bytes;
+  const size_t pg_bytes = st->workspace_bytes - scan_bytes;
   BPPSA_TRY(bppsa_forward(BPPSA_RNN_TANH, T, B, H, I, x, p, p + o_whh, p + o_bih, p + o_bhh, st->h, stream));
   BPPSA_TRY(bppsa_head_backward(B, H, C, st->h + (size_t)T * B * H, p + o_wout, p + o_bout, labels, st->seed,
                                 st->loss, g + o_wout, g + o_bout, stream));
@@ -161,13 +166,13 @@ extern "C" bppsa_status bppsa_rnn_train_step(int T, int B, int H, int I, int C, 
   if (st->Jt) {
     BPPSA_TRY(bppsa_build_jacobians(BPPSA_RNN_TANH, T, B, H, I, st->h, nullptr, nullptr, p + o_whh, nullptr,
                                     nullptr, st->Jt, stream));
-    BPPSA_TRY(bppsa_scan(T, B, H, st->Jt, st->seed, st->G, nullptr, st->workspace, st->workspace_bytes, stream));
+    BPPSA_TRY(bppsa_scan(T, B, H, st->Jt, st->seed, st->G, nullptr, st->workspace, scan_bytes, stream));
   } else {
-    BPPSA_TRY(bppsa_rnn_scan_fused(T, B, H, st->h, p + o_whh, st->seed, st->G, nullptr, st->workspace,
-                                   st->workspace_bytes, stream));
+    BPPSA_TRY(bppsa_rnn_scan_fused(T, B, H, st->h, p + o_whh, st->seed, st->G, nullptr, st->workspace, scan_bytes,
+                                   stream));
   }
   BPPSA_TRY(bppsa_param_grads(BPPSA_RNN_TANH, T, B, H, I, st->h, x, st->G, nullptr, nullptr, nullptr, nullptr, g,
-                              g + o_whh, g + o_bih, g + o_bhh, st->workspace, st->workspace_bytes, stream));
+                              g + o_whh, g + o_bih, g + o_bhh, pg_ws, pg_bytes, stream));
   return bppsa_adam_step((int64_t)bppsa_rnn_param_count(H, I, C), st->params, st->grads, st->adam_m, st->adam_v,
                          step, lr, beta1, beta2, eps, stream);
 }

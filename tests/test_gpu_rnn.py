@@ -68,6 +68,8 @@ def test_scan_matches_linear_scan(bp, T, B, H, want_g0):
     G_ref, g0_ref = oscan.linear_scan(jt, seed)
     g0 = torch.empty((B, H), dtype=torch.float32, device="cuda") if want_g0 else None
     G = bp.scan(to_gpu(jt), to_gpu(seed), g0=g0)
+    if H == 20:
+        bp.check_scan()                 # synchronises; raises if a bounded wait inside the scan expired
     torch.cuda.synchronize()
     assert rel_err(to_np(G), G_ref) <= TOL
     assert per_step_err(to_np(G), G_ref) <= 20 * TOL
@@ -130,6 +132,8 @@ def _end_to_end(bp, w, h32=None):
     G = bp.scan(Jt, seed, g0=g0)
     grads = bp.param_grads(bp.RNN_TANH, h, to_gpu(w["x"]), G)
     torch.cuda.synchronize()
+    if w["H"] == 20:
+        bp.check_scan()
     return to_np(G), to_np(g0), [to_np(g) for g in grads]
 
 

@@ -79,7 +79,7 @@ def _run_iterations(bp, T, B, iters, materialise, lr):
     for it in range(iters):
         x, labels = workloads.bitstream_batch(T, B, first_sample=it * B)
         loss = tr.step(to_gpu(x), to_gpu(labels), lr=lr)
-        torch.cuda.synchronize()
+        bp.check_scan(tr.workspace)          # synchronises; the scan's error word is still there
         l_ref, g_ref, p_ref, mom = otrain.rnn_iteration(p_ref, mom, x, labels, it + 1, lr=lr)
         out.append((float(to_np(loss)[0]), l_ref, {k: to_np(tr.view(tr.grads, k)).copy() for k in bp.RNN_PARAM_ORDER},
                     g_ref, {k: to_np(tr.view(tr.params, k)).copy() for k in bp.RNN_PARAM_ORDER}, dict(p_ref)))
