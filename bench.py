@@ -25,12 +25,12 @@ HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E bandwidth
 # HBM traffic of one scan_h20_kernel launch, from two `rocprofv3 --pmc` runs (FETCH_SIZE, then
 # WRITE_SIZE, KiB per dispatch), each scaled by what the same counter reads for the 768,000,000-byte
 # calibration copy (FETCH_SIZE reads 375,011.5 KiB for 750,000 KiB fetched: scale 2.000; WRITE_SIZE
-# reads 750,008.4 for 750,000 written: scale 1.000).  Offline figures: the counters cannot be read
+# reads 750,006.6 for 750,000 written: scale 1.000).  Offline figures: the counters cannot be read
 # inside this process.  Keyed by (T, B, H); the summaries are the profiles/*.txt of the same workloads.
-PMC_COPY_SCALE = {"FETCH_SIZE": 750000.0 / 375011.5703, "WRITE_SIZE": 750000.0 / 750007.4062}
+PMC_COPY_SCALE = {"FETCH_SIZE": 750000.0 / 375011.5703, "WRITE_SIZE": 750000.0 / 750006.6250}
 PMC_SCAN_KIB = {
-    (1000, 16, 20): {"FETCH_SIZE": 13619.4212, "WRITE_SIZE": 2346.5000},
-    (30000, 16, 20): {"FETCH_SIZE": 402714.2163, "WRITE_SIZE": 70381.9135},
+    (1000, 16, 20): {"FETCH_SIZE": 13651.1714, "WRITE_SIZE": 2362.0000},
+    (30000, 16, 20): {"FETCH_SIZE": 397965.4763, "WRITE_SIZE": 57932.9544},
 }
 
 

@@ -41,9 +41,16 @@ bppsa_status bppsa_launch_spgemm_numeric(int kind, const bppsa_csr& A, const bpp
                                          const int32_t* c_indptr, const int32_t* c_indices, float* c_data,
                                          int c_max_row, hipStream_t stream);
 
-// Adds a fingerprint of a[0..count) (values and their positions; `salt` tells arrays apart) to the
-// two 64-bit words at out (device).  The sums do not depend on the order of the additions.
-bppsa_status bppsa_launch_pattern_hash(const int32_t* a, int64_t count, unsigned long long salt,
-                                       unsigned long long* out, hipStream_t stream);
+// Adds a fingerprint of up to BPPSA_HASH_BATCH index arrays (values and their positions; `salt`
+// tells arrays apart) to the two 64-bit words at out (device), in one launch.  The sums do not
+// depend on the order of the additions.  The batch travels by value as a kernel argument.
+#define BPPSA_HASH_BATCH 64
+struct bppsa_hash_batch {
+  const int32_t* array[BPPSA_HASH_BATCH];
+  long long count[BPPSA_HASH_BATCH];
+  unsigned long long salt[BPPSA_HASH_BATCH];
+};
+bppsa_status bppsa_launch_pattern_hash(const bppsa_hash_batch& batch, int n, unsigned long long* out,
+                                       hipStream_t stream);
 
 constexpr int kBppsaMaxSpgemmCols = 1 << 20;  // LDS bitmap: one bit per column of B

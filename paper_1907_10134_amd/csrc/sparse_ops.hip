@@ -176,8 +176,10 @@ __device__ __forceinline__ unsigned long long mix64(unsigned long long x) {
 }
 
 __global__ void __launch_bounds__(256)
-pattern_hash_kernel(const int32_t* __restrict__ a, long long count, unsigned long long salt,
-                    unsigned long long* __restrict__ out) {
+pattern_hash_kernel(bppsa_hash_batch batch, unsigned long long* __restrict__ out) {
+  const int32_t* __restrict__ a = batch.array[blockIdx.y];
+  const long long count = batch.count[blockIdx.y];
+  const unsigned long long salt = batch.salt[blockIdx.y];
   unsigned long long h0 = 0, h1 = 0;
   const long long stride = (long long)gridDim.x * blockDim.x;
   for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += stride) {
@@ -190,7 +192,7 @@ pattern_hash_kernel(const int32_t* __restrict__ a, long long count, unsigned lon
     h0 += __shfl_down(h0, off, 64);
     h1 += __shfl_down(h1, off, 64);
   }
-  if ((threadIdx.x & 63) == 0) {
+  if ((threadIdx.x & 63) == 0 && (h0 | h1) != 0) {
     atomicAdd(out, h0);
     atomicAdd(out + 1, h1);
   }
@@ -528,12 +530,11 @@ bppsa_status bppsa_launch_spgemm_indices(const bppsa_csr& A, const bppsa_csr& B,
   return BPPSA_OK;
 }
 
-bppsa_status bppsa_launch_pattern_hash(const int32_t* a, int64_t count, unsigned long long salt,
-                                       unsigned long long* out, hipStream_t stream) {
-  if (count < 1) return BPPSA_OK;
-  long long blocks = (count + 256 * 8 - 1) / (256 * 8);
-  if (blocks > 1024) blocks = 1024;
-  pattern_hash_kernel<<<(int)blocks, 256, 0, stream>>>(a, (long long)count, salt, out);
+bppsa_status bppsa_launch_pattern_hash(const bppsa_hash_batch& batch, int n, unsigned long long* out,
+                                       hipStream_t stream) {
+  if (n < 1) return BPPSA_OK;
+  if (n > BPPSA_HASH_BATCH) return BPPSA_EINVAL;
+  pattern_hash_kernel<<<dim3(64, n), 256, 0, stream>>>(batch, out);
   BPPSA_CHECK_LAUNCH();
   return BPPSA_OK;
 }

@@ -384,9 +384,22 @@ extern "C" bppsa_status bppsa_spscan_plan_create_cached(bppsa_spscan_cache* cach
   // fingerprint of all row pointers and column indices, formed on the device
   unsigned long long key[2] = {0, 0};
   if (hipMemsetAsync(cache->d_key, 0, sizeof(key), s) != hipSuccess) return BPPSA_EHIP;
-  for (int k = 0; k < n; ++k) {
-    BPPSA_TRY(bppsa_launch_pattern_hash(Jt[k].indptr, (int64_t)Jt[k].rows + 1, 2ull * k + 1, cache->d_key, s));
-    if (Jt[k].nnz > 0) BPPSA_TRY(bppsa_launch_pattern_hash(Jt[k].indices, Jt[k].nnz, 2ull * k + 2, cache->d_key, s));
+  {
+    bppsa_hash_batch batch;
+    int filled = 0;
+    auto add = [&](const int32_t* a, long long count, unsigned long long salt) -> bppsa_status {
+      batch.array[filled] = a;
+      batch.count[filled] = count;
+      batch.salt[filled] = salt;
+      if (++filled < BPPSA_HASH_BATCH) return BPPSA_OK;
+      filled = 0;
+      return bppsa_launch_pattern_hash(batch, BPPSA_HASH_BATCH, cache->d_key, s);
+    };
+    for (int k = 0; k < n; ++k) {
+      BPPSA_TRY(add(Jt[k].indptr, (long long)Jt[k].rows + 1, 2ull * k + 1));
+      if (Jt[k].nnz > 0) BPPSA_TRY(add(Jt[k].indices, Jt[k].nnz, 2ull * k + 2));
+    }
+    BPPSA_TRY(bppsa_launch_pattern_hash(batch, filled, cache->d_key, s));
   }
   if (hipMemcpyAsync(key, cache->d_key, sizeof(key), hipMemcpyDeviceToHost, s) != hipSuccess ||
       hipStreamSynchronize(s) != hipSuccess)

@@ -12,7 +12,9 @@ def rel_err(got, ref):
     denom = np.max(np.abs(ref))
     if denom == 0.0:
         return float(np.max(np.abs(got)))
-    return float(np.max(np.abs(got - ref)) / denom)
+    value = float(np.max(np.abs(got - ref)) / denom)
+    _report("rel_err", value)
+    return value
 
 
 def per_step_err(got, ref, floor=1e-30):
@@ -23,7 +25,19 @@ def per_step_err(got, ref, floor=1e-30):
     keep = n >= floor
     if not np.any(keep):
         return 0.0
-    return float(np.max(np.max(np.abs(got - ref), axis=1)[keep] / n[keep]))
+    value = float(np.max(np.max(np.abs(got - ref), axis=1)[keep] / n[keep]))
+    _report("per_step_err", value)
+    return value
+
+
+def _report(what, value):
+    """With BPPSA_TEST_REPORT=<file> in the environment, every measured figure is appended to that
+    file with the name of the running test (the bounds in the tests are limits, not measurements)."""
+    import os
+    path = os.environ.get("BPPSA_TEST_REPORT")
+    if path:
+        with open(path, "a") as f:
+            f.write("%s %s %.3e\n" % (os.environ.get("PYTEST_CURRENT_TEST", "?").split(" ")[0], what, value))
 
 
 def to_gpu(a):
