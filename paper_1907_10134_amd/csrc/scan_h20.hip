@@ -409,14 +409,14 @@ __device__ __forceinline__ void up_sweep_upper(float* mat, int role, int slot, i
   if (role >= 2) {
     __builtin_amdgcn_s_setprio(2);
     wave_product(mat + toff(16 * (role - 2) + 15), mat + toff(16 * (role - 2) + 7), slot, q);
-    __builtin_amdgcn_s_setprio(0);
+    __builtin_amdgcn_s_setprio(1);
   }
   __syncthreads();
   if (role == 1) {
     __builtin_amdgcn_s_setprio(2);
     wave_product(mat + toff(31), mat + toff(15), slot, q);
     if (lo) wave_product(mat + toff(31), lo, slot, q);
-    __builtin_amdgcn_s_setprio(0);
+    __builtin_amdgcn_s_setprio(1);
   }
   __syncthreads();
 }
@@ -746,6 +746,9 @@ __device__ __forceinline__ void drain_queue(int qid, int nq, const Problem& pr, 
     const int m = (n - c0 < U) ? (n - c0) : U;   // real elements; the rest are identity tiles
     const GradOut out = {pr.G + ((size_t)(T - 1 - c0) * B + b) * H, B * H, m, stream_out};
 
+    // Everything up to the published total is what later units of this sample wait for; it runs
+    // at a higher wave priority than the down-sweeps of the other workgroups of the compute unit.
+    __builtin_amdgcn_s_setprio(1);
     float park[5][10];
     if (two) {
       // ---- first half: reduce, park the tree in registers, keep the total in LDS ---------------
@@ -777,6 +780,7 @@ __device__ __forceinline__ void drain_queue(int qid, int nq, const Problem& pr, 
     __syncthreads();
     if (interior && tid == 0) store_status<SCOPE>(pr.status + (size_t)b * nunit + k, kTotalReady);
     const int next = __builtin_amdgcn_readfirstlane(*sh.ticket_s);
+    __builtin_amdgcn_s_setprio(0);
 
     // ---- incoming vector, inclusive vector; the next unit's first half is requested ------------
     if (role == 3) {
