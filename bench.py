@@ -29,8 +29,8 @@ HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E bandwidth
 # inside this process.  Keyed by (T, B, H); the summaries are the profiles/*.txt of the same workloads.
 PMC_COPY_SCALE = {"FETCH_SIZE": 750000.0 / 375011.5703, "WRITE_SIZE": 750000.0 / 750006.6250}
 PMC_SCAN_KIB = {
-    (1000, 16, 20): {"FETCH_SIZE": 13651.1714, "WRITE_SIZE": 2362.0000},
-    (30000, 16, 20): {"FETCH_SIZE": 397965.4763, "WRITE_SIZE": 57932.9544},
+    (1000, 16, 20): {"FETCH_SIZE": 13651.1809, "WRITE_SIZE": 2362.0000},
+    (30000, 16, 20): {"FETCH_SIZE": 397468.7030, "WRITE_SIZE": 57931.9031},
 }
 
 

@@ -71,9 +71,9 @@ rnn_jacobians_h20_kernel(int tiles, int B, const float* __restrict__ h, const fl
 #pragma unroll
   for (int u = 0; u < 4; ++u) w[u] = w_hh[(j4 + u) * H + i];
   const int step = gridDim.x * kH20TilesPerPass;
-  // Four tiles per trip: the four 16-byte reads of h are issued before the first result is
-  // formed, so a thread waits for memory once per four stores instead of once per store.
-  constexpr int kTrip = 4;
+  // Eight tiles per trip: the eight 16-byte reads of h are issued before the first result is
+  // formed, so a thread waits for memory once per eight stores instead of once per store.
+  constexpr int kTrip = 8;
   for (int m0 = blockIdx.x * kH20TilesPerPass + slot; m0 < tiles; m0 += kTrip * step) {
     bj_v4f hv[kTrip];
 #pragma unroll
