@@ -21,6 +21,14 @@ FLAGS = [
 ]
 
 
+# Options of single files.  scan_h128.hip: MFMA results go to ordinary vector registers, because the
+# reduce kernel feeds the accumulators of one step to the next step as the B operand, which the
+# accumulation registers cannot be without a copy of all 64 per step (and twice the registers).
+FILE_FLAGS = {
+    "scan_h128.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
+}
+
+
 def sources():
     return sorted(f for f in os.listdir(CSRC) if f.endswith(".hip"))
 
@@ -33,7 +41,7 @@ def _compile(src: str, force: bool) -> str:
         newest = max(newest, os.path.getmtime(os.path.join(INCLUDE, "bppsa.h")))
         if os.path.getmtime(obj) > newest:
             return obj
-    cmd = [HIPCC, *FLAGS, "-c", src_path, "-o", obj]
+    cmd = [HIPCC, *FLAGS, *FILE_FLAGS.get(src, []), "-c", src_path, "-o", obj]
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
         raise RuntimeError("hipcc failed on %s:\n%s\n%s" % (src, res.stdout, res.stderr))

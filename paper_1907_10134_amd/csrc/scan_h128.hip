@@ -2,200 +2,139 @@
 //
 // At this size a matrix-matrix node of the up-sweep (Algorithm 1, a[r] <- a[r] a[l]) is
 // 4.2 MFLOP against 64 KB of operand traffic: it belongs on the matrix cores.  The reduce
-// kernel keeps the running product of a segment in MFMA accumulators and streams one
-// transposed Jacobian per step through LDS; the apply kernel walks a segment with
-// matrix-vector products (the down-sweep side), streaming each Jacobian once with the next
-// one already in flight.
-#include "bppsa_internal.h"
-#include "scan_plan.h"
+// kernel keeps the running product of a segment in registers, as MFMA results that are the next
+// step's B operands, and streams one transposed Jacobian per step through LDS; the apply kernel
+// walks a segment with matrix-vector products (the down-sweep side), streaming each Jacobian
+// once with the next one already in flight.
+//
+// This file is compiled with MFMA results in ordinary vector registers (see the build script):
+// an accumulation register cannot be a B operand.
+#include "scan_h128_common.h"
 
 namespace {
-
-typedef float v4f __attribute__((ext_vector_type(4)));
-typedef float v16f __attribute__((ext_vector_type(16)));
-
-constexpr int H = 128;
-constexpr int HH = H * H;
-constexpr int LS = H + 4;            // LDS row stride in floats: rows 8 apart share a bank, so the
-                                     // 16-byte reads of 8 consecutive rows tile all 32 banks
-constexpr int kThreads = 256;
-constexpr int kChunks = HH / 4 / kThreads;   // 16-byte pieces of a tile per thread (16)
-
-__device__ __forceinline__ void seg_bounds(int T, int t_min, int S, int seg, int& lo, int& hi) {
-  lo = t_min + seg * S;
-  hi = min(lo + S, T) - 1;
-}
-
-// GRU transposed Jacobians generated in place of being read (Appendix E):
-//   Jt[i][j] = W_hr[j][i] a_j + W_hn[j][i] c_j + W_hz[j][i] e_j + [i == j] z_j
-// with the per-step coefficient vectors (a, c, e, z) of bppsa_gru_coefs_h128 and the three
-// recurrent matrices transposed, wT[g][i][j] (g = r, n, z).  Both kernels below give thread tid
-// the 16-byte pieces e = tid + 256 q of a tile, i.e. rows tid / 32 + 8 q and columns
-// 4 (tid % 32) .. + 3: the same places in every tile, so the thread keeps its 3 x 16 pieces of
-// the weights in registers for the whole segment and a tile costs it four coefficient reads and
-// 192 multiply-adds instead of 256 bytes from HBM.
-struct GruWeights {
-  v4f r[kChunks], n[kChunks], z[kChunks];
-};
-struct GruCoef {
-  v4f a, c, e, z;
-};
-
-__device__ __forceinline__ void load_gru_weights(const float* __restrict__ wT, int tid, GruWeights& w) {
-#pragma unroll
-  for (int q = 0; q < kChunks; ++q) {
-    const int e = tid + q * kThreads;
-    w.r[q] = reinterpret_cast<const v4f*>(wT)[e];
-    w.n[q] = reinterpret_cast<const v4f*>(wT + HH)[e];
-    w.z[q] = reinterpret_cast<const v4f*>(wT + 2 * HH)[e];
-  }
-}
-__device__ __forceinline__ GruCoef load_gru_coef(const float* __restrict__ coef, size_t row, int tid) {
-  const v4f* c = reinterpret_cast<const v4f*>(coef + row * 4 * H) + (tid & 31);
-  return GruCoef{c[0], c[H / 4], c[2 * (H / 4)], c[3 * (H / 4)]};
-}
-__device__ __forceinline__ v4f gru_piece(const GruWeights& w, const GruCoef& cf, int tid, int q) {
-  v4f o = w.r[q] * cf.a + w.n[q] * cf.c + w.z[q] * cf.e;
-  const int d = (tid >> 5) + 8 * q - 4 * (tid & 31);      // row minus first column of the piece
-#pragma unroll
-  for (int u = 0; u < 4; ++u) o[u] += (d == u) ? cf.z[u] : 0.f;
-  return o;
-}
 
 // P <- J P for J = Jt[hi-1], ..., Jt[lo], starting from P = Jt[hi]; tot[seg][b] = P.
 //
 // v_mfma_f32_32x32x2_f32 contracts two k values per issue: lane l supplies A[i = l % 32][k(l / 32)]
 // and B[k(l / 32)][j = l % 32], and holds D[8 (v / 4) + 4 (l / 32) + v % 4][l % 32] in
 // accumulator register v.  Any assignment of the 128 k values to (issue, lane half) is valid as
-// long as A and B agree; here issue 4 g + s of lane half h takes k = 8 g + 4 h + s, so that one
-// 16-byte LDS read per operand feeds four issues.  A is stored [i][k] and the running product
-// is stored transposed, [j][k], which is also the order in which the accumulators come out.
-// Each of the four waves owns a 64 x 64 quadrant of the product (2 x 2 MFMA blocks).
-// GEN: the Jacobians are generated from (coef, wT) instead of read from Jt.
-template <bool GEN>
+// long as A and B agree.  Here issue (kb, q, s) of lane half h takes k = 32 kb + 8 q + 4 h + s,
+// which is exactly the row that accumulator register 4 q + s of row-block kb holds in that lane
+// half: the running product never leaves the registers.  Each of the four waves owns a strip of
+// 32 columns of P (four 32 x 32 accumulator blocks) and therefore holds every k of its columns;
+// the accumulators of one step are the B operands of the next, and two sets alternate.  Only the
+// Jacobian goes through LDS, [i][k] with one 16-byte read per row-block feeding four issues, in
+// two buffers: while a step reads one, the Jacobian of the next step is written to the other
+// piece by piece between the issues (from registers filled one step earlier), and the registers
+// are refilled from memory for the step after.  A step therefore has one barrier
+// and nothing but its 256 issues on the critical path.
+//
+// One step: nw = A old, A read from As; piece g of the next Jacobian goes to An during k group g.
+// The scheduling barriers pin the order written here.  Left alone, the scheduler puts the LDS
+// reads of the next group behind the last issue that uses the registers they could share, and
+// the memory requests in one burst ahead of the first issue, which leaves the matrix pipe idle
+// for a fifth of the step.
+__device__ __forceinline__ void reduce_h128_step(const float* __restrict__ As, float* __restrict__ An,
+                                                 const v4f* __restrict__ refill, v4f (&pre)[kChunks], int tid,
+                                                 int l32, int hsel, const v16f (&old)[4], v16f (&nw)[4]) {
+  const float* arow = As + l32 * LS + 4 * hsel;
+  float* stage = An + (tid >> 5) * LS + (tid & 31) * 4;      // piece g lies 8 g rows further down
+  const v16f zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  v4f a4[2][4];
+#pragma unroll
+  for (int bi = 0; bi < 4; ++bi) a4[0][bi] = *reinterpret_cast<const v4f*>(arow + 32 * bi * LS);
+#pragma unroll
+  for (int g = 0; g < 16; ++g) {                 // g = 4 kb + q
+    const int cur = g & 1;
+    if (g < 15) {                                // operands of the next k group
+#pragma unroll
+      for (int bi = 0; bi < 4; ++bi)
+        a4[cur ^ 1][bi] = *reinterpret_cast<const v4f*>(arow + 32 * bi * LS + 8 * (g + 1));
+    }
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      if (s == 1) {
+        *reinterpret_cast<v4f*>(stage + 8 * g * LS) = pre[g];
+      } else if (s == 2) {
+        pre[g] = refill[tid + g * kThreads];
+      }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int bi = 0; bi < 4; ++bi)
+        nw[bi] = __builtin_amdgcn_mfma_f32_32x32x2f32(a4[cur][bi][s], old[g >> 2][4 * (g & 3) + s],
+                                                      (g == 0 && s == 0) ? zero : nw[bi], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+}
+
 __global__ void __launch_bounds__(kThreads, 1)
 reduce_h128_kernel(int T, int B, int t_min, int S, int seg_begin, const float* __restrict__ Jt,
-                   float* __restrict__ tot, const float* __restrict__ coef, const float* __restrict__ wT) {
+                   float* __restrict__ tot) {
   extern __shared__ __attribute__((aligned(16))) float smem[];
-  float* As = smem;                 // [128][LS]  A[i][k]
-  float* Bt = smem + H * LS;        // [128][LS]  P^T: Bt[j][k] = P[k][j]
+  float* As0 = smem;                // [128][LS]  A[i][k], two buffers
+  float* As1 = smem + H * LS;
   const int tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63;
-  const int wr = wave >> 1, wc = wave & 1;
   const int l32 = lane & 31, hsel = lane >> 5;
   const int seg = seg_begin + blockIdx.x;
   const int b = blockIdx.y;
   int lo, hi;
   seg_bounds(T, t_min, S, seg, lo, hi);
 
-  GruWeights gw;
-  GruCoef cf;
-  if (GEN) {
-    load_gru_weights(wT, tid, gw);
-    cf = load_gru_coef(coef, (size_t)hi * B + b, tid);
-  }
-  // P = Jt[hi], written transposed (once per segment)
-  {
-    const float* src = GEN ? nullptr : Jt + ((size_t)hi * B + b) * HH;
+  v4f pre[kChunks];
+  // tile t into the registers of its pieces; t is clamped to the segment, so the steps near the
+  // end refill and stage a tile nobody reads instead of branching
+  auto tile = [&](int t) { return reinterpret_cast<const v4f*>(Jt + ((size_t)max(t, lo) * B + b) * HH); };
+  auto fetch = [&](int t) {
+    const v4f* src = tile(t);
+#pragma unroll
+    for (int r = 0; r < kChunks; ++r) pre[r] = src[tid + r * kThreads];
+  };
+  auto stage_all = [&](float* As) {
 #pragma unroll
     for (int r = 0; r < kChunks; ++r) {
       const int e = tid + r * kThreads;
-      const int k = e >> 5, j4 = (e & 31) * 4;
-      const v4f x = GEN ? gru_piece(gw, cf, tid, r) : reinterpret_cast<const v4f*>(src)[e];
-      Bt[(j4 + 0) * LS + k] = x[0];
-      Bt[(j4 + 1) * LS + k] = x[1];
-      Bt[(j4 + 2) * LS + k] = x[2];
-      Bt[(j4 + 3) * LS + k] = x[3];
+      *reinterpret_cast<v4f*>(As + (e >> 5) * LS + (e & 31) * 4) = pre[r];
     }
-  }
-  v16f acc[2][2];
-  v4f pre[GEN ? 1 : kChunks];
-  if (hi - 1 >= lo) {
-    if (GEN) {
-      cf = load_gru_coef(coef, (size_t)(hi - 1) * B + b, tid);
-    } else {
-      const float* src = Jt + ((size_t)(hi - 1) * B + b) * HH;
+  };
+  // P = Jt[hi] through LDS into the accumulator layout: register v of row-block kb holds row
+  // 32 kb + 8 (v / 4) + 4 hsel + v % 4 of column 32 wave + l32
+  v16f P[4], Q[4];
+  fetch(hi);
+  stage_all(As1);
+  fetch(hi - 1);
+  __syncthreads();
 #pragma unroll
-      for (int r = 0; r < kChunks; ++r) pre[r] = reinterpret_cast<const v4f*>(src)[tid + r * kThreads];
-    }
-  }
-  for (int t = hi - 1; t >= lo; --t) {
-    // the prefetched (or generated) Jacobian becomes the A operand
+  for (int kb = 0; kb < 4; ++kb)
 #pragma unroll
-    for (int r = 0; r < kChunks; ++r) {
-      const int e = tid + r * kThreads;
-      *reinterpret_cast<v4f*>(As + (e >> 5) * LS + (e & 31) * 4) = GEN ? gru_piece(gw, cf, tid, r) : pre[r];
-    }
+    for (int v = 0; v < 16; ++v)
+      P[kb][v] = As1[(32 * kb + 8 * (v >> 2) + 4 * hsel + (v & 3)) * LS + 32 * wave + l32];
+  stage_all(As0);
+  fetch(hi - 2);
+  __syncthreads();
+  // Step i multiplies by Jt[hi-1-i], read from buffer i % 2.  Buffer (i + 1) % 2 was last read in
+  // step i - 1 (or above, for P), which every wave has left, so the tile of step i + 1 may be
+  // written to it during step i; the registers then take the tile of step i + 2.
+  const int steps = hi - lo;
+  for (int i = 0; i < steps; i += 2) {
+    reduce_h128_step(As0, As1, tile(hi - 3 - i), pre, tid, l32, hsel, P, Q);
     __syncthreads();
-    if (t - 1 >= lo) {
-      if (GEN) {
-        cf = load_gru_coef(coef, (size_t)(t - 1) * B + b, tid);
-      } else {
-        const float* src = Jt + ((size_t)(t - 1) * B + b) * HH;
-#pragma unroll
-        for (int r = 0; r < kChunks; ++r) pre[r] = reinterpret_cast<const v4f*>(src)[tid + r * kThreads];
-      }
-    }
-#pragma unroll
-    for (int bi = 0; bi < 2; ++bi)
-#pragma unroll
-      for (int bj = 0; bj < 2; ++bj)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) acc[bi][bj][v] = 0.f;
-    const float* arow = As + (64 * wr + l32) * LS + 4 * hsel;
-    const float* brow = Bt + (64 * wc + l32) * LS + 4 * hsel;
-    v4f a4[2][2], b4[2][2];
-    a4[0][0] = *reinterpret_cast<const v4f*>(arow);
-    a4[0][1] = *reinterpret_cast<const v4f*>(arow + 32 * LS);
-    b4[0][0] = *reinterpret_cast<const v4f*>(brow);
-    b4[0][1] = *reinterpret_cast<const v4f*>(brow + 32 * LS);
-#pragma unroll
-    for (int g = 0; g < 16; ++g) {
-      const int cur = g & 1;
-      if (g < 15) {                               // operands of the next k group
-        a4[cur ^ 1][0] = *reinterpret_cast<const v4f*>(arow + 8 * (g + 1));
-        a4[cur ^ 1][1] = *reinterpret_cast<const v4f*>(arow + 32 * LS + 8 * (g + 1));
-        b4[cur ^ 1][0] = *reinterpret_cast<const v4f*>(brow + 8 * (g + 1));
-        b4[cur ^ 1][1] = *reinterpret_cast<const v4f*>(brow + 32 * LS + 8 * (g + 1));
-      }
-#pragma unroll
-      for (int s = 0; s < 4; ++s)
-#pragma unroll
-        for (int bi = 0; bi < 2; ++bi)
-#pragma unroll
-          for (int bj = 0; bj < 2; ++bj)
-            acc[bi][bj] = __builtin_amdgcn_mfma_f32_32x32x2f32(a4[cur][bi][s], b4[cur][bj][s], acc[bi][bj], 0, 0, 0);
-    }
-    __syncthreads();                              // every wave has finished reading As and Bt
-    if (t > lo) {
-      // the product becomes the next B operand: accumulator registers 4 q .. 4 q + 3 are four
-      // consecutive k of one column
-#pragma unroll
-      for (int bi = 0; bi < 2; ++bi)
-#pragma unroll
-        for (int bj = 0; bj < 2; ++bj)
-#pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            const v4f x = {acc[bi][bj][4 * q], acc[bi][bj][4 * q + 1], acc[bi][bj][4 * q + 2], acc[bi][bj][4 * q + 3]};
-            *reinterpret_cast<v4f*>(Bt + (64 * wc + 32 * bj + l32) * LS + 64 * wr + 32 * bi + 8 * q + 4 * hsel) = x;
-          }
+    if (i + 1 < steps) {
+      reduce_h128_step(As1, As0, tile(hi - 4 - i), pre, tid, l32, hsel, Q, P);
+      __syncthreads();
     }
   }
-  float* dst = tot + ((size_t)seg * B + b) * HH;
-  if (hi > lo) {
+  // an odd number of steps leaves the product in Q
+  float* dst = tot + ((size_t)seg * B + b) * HH + 32 * wave + l32;
+  const bool inQ = (steps & 1) != 0;              // uniform
 #pragma unroll
-    for (int bi = 0; bi < 2; ++bi)
+  for (int kb = 0; kb < 4; ++kb)
 #pragma unroll
-      for (int bj = 0; bj < 2; ++bj)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int row = 64 * wr + 32 * bi + 8 * (v >> 2) + 4 * hsel + (v & 3);
-          dst[row * H + 64 * wc + 32 * bj + l32] = acc[bi][bj][v];
-        }
-  } else {                                        // one-step segment: the total is Jt[hi] itself
-    __syncthreads();
-    for (int e = tid; e < HH; e += kThreads) dst[e] = Bt[(e & (H - 1)) * LS + (e >> 7)];
-  }
+    for (int v = 0; v < 16; ++v) {
+      const int row = 32 * kb + 8 * (v >> 2) + 4 * hsel + (v & 3);
+      dst[row * H] = inQ ? Q[kb][v] : P[kb][v];
+    }
 }
 
 // v <- Jt[t] v for t = hi..lo, writing g[t] = v to G[t-1] (g0 when t == 0).
@@ -286,20 +225,13 @@ apply_h128_kernel(int T, int B, int t_min, int S, int seg_begin, const float* __
 bppsa_status bppsa_reduce_h128(int T, int B, int t_min, int S, int seg_begin, int seg_count,
                                const float* Jt, float* tot, hipStream_t s, const bppsa_gru_tiles* gen) {
   if (seg_count <= 0) return BPPSA_OK;
+  if (gen) return bppsa_reduce_h128_gen(T, B, t_min, S, seg_begin, seg_count, tot, s, gen);
   const size_t lds = (size_t)2 * H * LS * sizeof(float);
   // set on every call: the attribute belongs to the current device's copy of the kernel, and the
   // library keeps no per-process record of which devices it has run on
-  if (gen) {
-    BPPSA_HIP_TRY(hipFuncSetAttribute((const void*)reduce_h128_kernel<true>,
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    reduce_h128_kernel<true><<<dim3(seg_count, B), kThreads, lds, s>>>(T, B, t_min, S, seg_begin, nullptr, tot,
-                                                                       gen->coef, gen->wT);
-  } else {
-    BPPSA_HIP_TRY(hipFuncSetAttribute((const void*)reduce_h128_kernel<false>,
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    reduce_h128_kernel<false><<<dim3(seg_count, B), kThreads, lds, s>>>(T, B, t_min, S, seg_begin, Jt, tot,
-                                                                        nullptr, nullptr);
-  }
+  BPPSA_HIP_TRY(hipFuncSetAttribute((const void*)reduce_h128_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    (int)lds));
+  reduce_h128_kernel<<<dim3(seg_count, B), kThreads, lds, s>>>(T, B, t_min, S, seg_begin, Jt, tot);
   BPPSA_CHECK_LAUNCH();
   return BPPSA_OK;
 }

@@ -66,6 +66,9 @@ bppsa_status bppsa_scan_generic(int T, int B, int H, const float* Jt, const floa
 // ---- matrix-core kernels for H = 128 (used by the generic scan's reduce and apply steps) ----
 bppsa_status bppsa_reduce_h128(int T, int B, int t_min, int S, int seg_begin, int seg_count,
                                const float* Jt, float* tot, hipStream_t s, const bppsa_gru_tiles* gen = nullptr);
+// The same totals with the tiles generated (gen is not null); called by bppsa_reduce_h128.
+bppsa_status bppsa_reduce_h128_gen(int T, int B, int t_min, int S, int seg_begin, int seg_count, float* tot,
+                                   hipStream_t s, const bppsa_gru_tiles* gen);
 bppsa_status bppsa_apply_h128(int T, int B, int t_min, int S, int seg_begin, int seg_count,
                               const float* Jt, const float* vin, int vin_is_seed, float* G, float* g0,
                               float* v_out, hipStream_t s, const bppsa_gru_tiles* gen = nullptr);
