@@ -239,8 +239,9 @@ def copy_calibration(bp, steps):
 def gru_workload(bp, workloads, steps):
     """configs[3] (GRU H=128, T=4096, B=16): per-call times of the three hot-path calls.
 
-    The scan is bound by the fp32 matrix cores here: (nseg - 2) interior segments of S steps
-    each cost S - 1 matrix-matrix products of 2 H^3 FLOP per sample."""
+    The scan's schedule (how many steps nearest the seed one serial matrix-vector chain per sample
+    walks, how many segments get matrix-matrix totals) is the library's own choice, read back with
+    bppsa_scan_h128_schedule; a total costs S - 1 products of 2 H^3 FLOP per sample."""
     import torch
     w = workloads.config_inputs(3)
     T, B, H, I = w["T"], w["B"], w["H"], w["I"]
@@ -277,9 +278,9 @@ def gru_workload(bp, workloads, steps):
     torch.cuda.synchronize()
     parts = {name: statistics.mean(e[i].elapsed_time(e[i + 1]) for e in evs)
              for i, name in enumerate(("build_jacobians_ms", "scan_ms", "param_grads_ms"))}
-    S = 64
-    nseg = -(-(T - 1) // S)
-    mm = (nseg - 2) * (S - 1) * B
+    sched = bp.scan_h128_schedule(T, B, want_g0=False, generated=False)
+    fsched = bp.scan_h128_schedule(T, B, want_g0=False, generated=True)
+    mm = sched["matrix_products"]
     flop = mm * 2 * H ** 3 + T * B * 2 * H * H
     tf = flop / (parts["scan_ms"] * 1e-3) / 1e12
     # the same backward pass with the Jacobians generated inside the scan (no Jt array)
@@ -299,6 +300,9 @@ def gru_workload(bp, workloads, steps):
     return {"workload": "gru_H128_I1_T4096_B16 (configs[3])", **{k: round(v, 4) for k, v in parts.items()},
             "fused_scan_ms": round(fused_ms, 4),
             "fused_vs_build_plus_scan": round((parts["build_jacobians_ms"] + parts["scan_ms"]) / fused_ms, 3),
+            "schedule": {k: sched[k] for k in ("segment_steps", "chain_steps", "slab_segments", "slabs")},
+            "fused_schedule": {k: fsched[k] for k in ("segment_steps", "chain_steps", "slab_segments", "slabs",
+                                                      "matrix_products")},
             "scan_matrix_products": mm, "scan_flop": flop, "scan_tflops": round(tf, 2),
             "frac_of_fp32_mfma_peak": round(tf / 157.3, 4),
             "scan_bytes_min": T * B * (4 * H * H + 4 * H), "jacobian_bytes": 4 * T * B * H * H}

@@ -473,6 +473,45 @@ bppsa_status bppsa_scan_h20_diag(int T, int B, const float* Jt, const float* see
                                  int absent_dies, int unit_halves, int64_t* lookback_stats);
 
 /*
+ * How bppsa_scan (generated = 0) or bppsa_gru_scan_fused (generated = 1) walks a chain of T steps
+ * of H = 128 for B samples on the current device.  The chain is cut into segments of
+ * `segment_steps` steps (Section 5.3's hybrid schedule); the `chain_steps` steps nearest the seed
+ * are walked by one serial matrix-vector chain per sample while the totals of the remaining
+ * segments are formed with matrix-matrix products, `slab_segments` segments at a time
+ * (`slabs` slabs; 0 when no slab is formed, or when the batch alone fills the device and the
+ * totals of all segments are formed at once and scanned recursively).  `matrix_products` counts
+ * the H x H matrix-matrix products of the call, `model_us` is the estimate the choice was made
+ * on (0 where no choice is made).  Host only, no device work.
+ * Errors: BPPSA_EINVAL (T or B below 1, out NULL).
+ */
+typedef struct {
+  int segment_steps;
+  int segments;
+  int chain_steps;
+  int slab_segments;
+  int slabs;
+  int64_t matrix_products;
+  double model_us;
+} bppsa_h128_schedule;
+bppsa_status bppsa_scan_h128_schedule(int T, int B, int want_g0, int generated, bppsa_h128_schedule* out);
+
+/*
+ * bppsa_scan at H = 128 with the schedule forced, for tests and for measurement; the gradients
+ * are those of bppsa_scan (same kernels, same workspace size).
+ *   chain_segments : segments nearest the seed walked by the serial chain (clamped to the number
+ *                    of segments; all of them = no matrix-matrix product).  0 = the form without
+ *                    the serial chain (totals of all interior segments, scanned recursively).
+ *   slab_segments  : segments per slab of totals; 0 = as many as fill the compute units that the
+ *                    serial chains leave free.  Raised if more than 32 slabs would result.
+ * Errors: those of bppsa_scan; BPPSA_EUNSUPPORTED if chain_segments > 0 and the device has fewer
+ * than 2 B compute units (the serial chains take one each).
+ */
+bppsa_status bppsa_scan_h128_diag(int T, int B, const float* Jt, const float* seed,
+                                  float* G, float* g0,
+                                  void* workspace, size_t workspace_bytes, void* stream,
+                                  int chain_segments, int slab_segments);
+
+/*
  * Plain streaming copy dst[i] = src[i] of n fp32 values (n a multiple of 4,
  * both pointers 16-byte aligned, non-overlapping).  It moves exactly 4n bytes
  * in and 4n bytes out of HBM, which makes it the unit against which hardware

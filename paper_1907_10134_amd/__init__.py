@@ -10,6 +10,6 @@ from .binding import (  # noqa: F401
     BppsaError, RNN_TANH, GRU, forward, head_seed, build_jacobians, scan,
     scan_workspace_bytes, param_grads, param_grads_workspace_bytes, lib_path,
     CsrMatrix, csr_conv3x3, csr_conv2d, csr_linear, csr_relu, csr_maxpool2x2, spmv, SpscanPlan, SpscanCache, spscan,
-    calibration_copy, rnn_scan_fused, scan_static, scan_h20_diag,
+    calibration_copy, rnn_scan_fused, scan_static, scan_h20_diag, scan_h128_diag, scan_h128_schedule,
     check_scan, gru_scan_fused, gru_scan_fused_workspace_bytes, head_backward, adam_step, rnn_param_count, RnnTrainer, RNN_PARAM_ORDER,
 )

@@ -46,6 +46,10 @@ def _load(path=_LIB_PATH):
     lib.bppsa_scan.argtypes = [c_int] * 3 + [c_void_p] * 5 + [c_size_t, c_void_p]
     lib.bppsa_scan_h20_diag.restype = c_int
     lib.bppsa_scan_h20_diag.argtypes = [c_int] * 2 + [c_void_p] * 5 + [c_size_t, c_void_p, c_int, c_int, c_void_p]
+    lib.bppsa_scan_h128_diag.restype = c_int
+    lib.bppsa_scan_h128_diag.argtypes = [c_int] * 2 + [c_void_p] * 5 + [c_size_t, c_void_p, c_int, c_int]
+    lib.bppsa_scan_h128_schedule.restype = c_int
+    lib.bppsa_scan_h128_schedule.argtypes = [c_int] * 4 + [ctypes.POINTER(H128Schedule)]
     lib.bppsa_scan_static.restype = c_int
     lib.bppsa_scan_static.argtypes = [c_int] * 3 + [c_void_p] * 5
     lib.bppsa_rnn_scan_fused.restype = c_int
@@ -133,6 +137,12 @@ class CsrDesc(ctypes.Structure):
     """Mirror of the C struct bppsa_csr (host struct, device array pointers)."""
     _fields_ = [("rows", ctypes.c_int32), ("cols", ctypes.c_int32), ("nnz", ctypes.c_int64),
                 ("indptr", ctypes.c_void_p), ("indices", ctypes.c_void_p), ("data", ctypes.c_void_p)]
+
+
+class H128Schedule(ctypes.Structure):
+    """bppsa_h128_schedule."""
+    _fields_ = [(k, ctypes.c_int32) for k in ("segment_steps", "segments", "chain_steps", "slab_segments", "slabs")] + \
+               [("matrix_products", ctypes.c_int64), ("model_us", ctypes.c_double)]
 
 
 class Conv2dGeometry(ctypes.Structure):
@@ -279,6 +289,29 @@ def scan_h20_diag(Jt, seed, G=None, g0=None, workspace=None, stream=None, absent
                                     int(absent_dies), int(unit_halves), _ptr(lookback_stats, torch.int64)),
            "bppsa_scan_h20_diag")
     return G
+
+
+def scan_h128_diag(Jt, seed, G=None, g0=None, workspace=None, stream=None, chain_segments=0, slab_segments=0):
+    """bppsa_scan_h128_diag: the H = 128 scan with a forced schedule (segments walked by the serial
+    chain, segments per slab of totals)."""
+    T, B, H, _ = Jt.shape
+    if G is None:
+        G = torch.empty((T, B, H), dtype=torch.float32, device=Jt.device)
+    if workspace is None:
+        workspace = _workspace(scan_workspace_bytes(T, B, H), Jt.device, stream)
+    _check(_lib.bppsa_scan_h128_diag(T, B, _ptr(Jt), _ptr(seed), _ptr(G), _ptr(g0), workspace.data_ptr(),
+                                     workspace.numel() * workspace.element_size(), _stream(stream),
+                                     int(chain_segments), int(slab_segments)),
+           "bppsa_scan_h128_diag")
+    return G
+
+
+def scan_h128_schedule(T, B, want_g0=False, generated=False):
+    """bppsa_scan_h128_schedule as a dict: how bppsa_scan (or bppsa_gru_scan_fused) walks such a chain."""
+    out = H128Schedule()
+    _check(_lib.bppsa_scan_h128_schedule(int(T), int(B), int(bool(want_g0)), int(bool(generated)), ctypes.byref(out)),
+           "bppsa_scan_h128_schedule")
+    return {name: getattr(out, name) for name, _ in H128Schedule._fields_}
 
 
 def scan_static(Jt, seed, G, g0=None, stream=None):

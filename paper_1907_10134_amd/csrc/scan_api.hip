@@ -80,6 +80,68 @@ extern "C" bppsa_status bppsa_scan_h20_diag(int T, int B, const float* Jt, const
                              reinterpret_cast<long long*>(lookback_stats), (hipStream_t)stream);
 }
 
+// Matrix-matrix products of the two-level form (every interior segment of every level reduced).
+static long long two_level_products(int n, int B) {
+  const int S = bppsa_generic_segment(128);
+  long long total = 0;
+  while (n > S) {
+    const int nseg = bppsa_ceil_div(n, S);
+    if (nseg > 2) total += (long long)(nseg - 2) * (S - 1) * B;
+    n = nseg - 2;                                  // the chain of totals, its first element being the seed side
+  }
+  return total;
+}
+
+extern "C" bppsa_status bppsa_scan_h128_schedule(int T, int B, int want_g0, int generated,
+                                                 bppsa_h128_schedule* out) {
+  if (T < 1 || B < 1 || !out) return BPPSA_EINVAL;
+  const int S = bppsa_generic_segment(128);
+  const int n = T - (want_g0 ? 0 : 1);
+  const int nseg = n > 0 ? bppsa_ceil_div(n, S) : 0;
+  *out = bppsa_h128_schedule{};
+  out->segment_steps = S;
+  out->segments = nseg;
+  if (n <= S) {                                    // one matrix-vector pass
+    out->chain_steps = n > 0 ? n : 0;
+    return BPPSA_OK;
+  }
+  const bppsa_h128_plan plan = bppsa_plan_h128(n, B, bppsa_compute_units(), generated != 0);
+  const int top = n - (nseg - 1) * S;
+  if (plan.chain_segments == 0) {
+    out->chain_steps = top;
+    out->matrix_products = two_level_products(n, B);
+    return BPPSA_OK;
+  }
+  out->chain_steps = top + (plan.chain_segments - 1) * S;
+  if (plan.chain_segments < nseg) {
+    out->slab_segments = plan.slab;
+    out->slabs = plan.slabs;
+    out->matrix_products = (long long)(nseg - plan.chain_segments - 1) * (S - 1) * B;
+  }
+  out->model_us = plan.model_us;
+  return BPPSA_OK;
+}
+
+extern "C" bppsa_status bppsa_scan_h128_diag(int T, int B, const float* Jt, const float* seed, float* G, float* g0,
+                                             void* workspace, size_t workspace_bytes, void* stream,
+                                             int chain_segments, int slab_segments) {
+  if (T < 1 || B < 1 || chain_segments < 0 || slab_segments < 0) return BPPSA_EINVAL;
+  if (!Jt || !seed || !G) return BPPSA_EINVAL;
+  if (bppsa_mul_overflows(T, B, 128, 128)) return BPPSA_EOVERFLOW;
+  if (B > 65535) return BPPSA_ESHAPE;
+  const size_t need = scan_ws_bytes(T, B, 128);
+  if (need > 256 && (!workspace || workspace_bytes < need)) return BPPSA_EWORKSPACE;
+  if (workspace && ((uintptr_t)workspace & 255)) return BPPSA_EINVAL;
+  const int n = T - (g0 ? 0 : 1);
+  bppsa_h128_plan plan = {0, 0, 0, 0.0};
+  if (chain_segments > 0) {
+    // the serial chain needs a compute unit per sample beside the matrix-core work
+    if (bppsa_compute_units() < 2 * B) return BPPSA_EUNSUPPORTED;
+    plan = bppsa_plan_h128(n, B, bppsa_compute_units(), false, chain_segments, slab_segments);
+  }
+  return bppsa_scan_generic(T, B, 128, Jt, seed, G, g0, workspace, (hipStream_t)stream, nullptr, &plan);
+}
+
 extern "C" bppsa_status bppsa_scan_static(int T, int B, int H, const float* Jt, const float* seed,
                                           float* G, float* g0, void* stream) {
   if (T < 1 || B < 1 || H < 1) return BPPSA_EINVAL;

@@ -175,7 +175,7 @@ bppsa_status launch_apply(int T, int B, int H, int t_min, int S, int seg_begin, 
 // device, created on first use and kept until the process ends.  `lock` is held while a call
 // enqueues work that uses them, so that the records and waits of two host threads do not
 // interleave.
-constexpr int kMaxSlabs = 32;
+constexpr int kMaxSlabs = BPPSA_H128_MAX_SLABS;
 struct SideStream {
   hipStream_t stream;
   hipEvent_t fork, join, slab[kMaxSlabs];
@@ -202,18 +202,21 @@ SideStream* side_stream() {
   return &table[dev];
 }
 
-// H = 128, long chains: the matrix-matrix totals (bound by the matrix cores, little memory
-// traffic) and the matrix-vector passes (bound by HBM, little arithmetic) run side by side.
-// The interior segments are cut into slabs, nearest the seed first, each slab filling the
-// device once.  The caller's stream forms the totals slab by slab; a second stream follows
-// one slab behind: chain of the slab's totals from the vector handed on by the previous slab,
-// then the slab's own matrix-vector pass.  A workgroup of either kind fits beside the other
-// on a compute unit (188 + 148 registers per lane, 135 KB + 1 KB of LDS).
+// H = 128, long chains: the schedule of bppsa_h128_plan.  A second stream walks the serial chain of
+// the segments nearest the seed (one 1024-thread workgroup per sample, which has its compute unit
+// to itself) while the caller's stream forms the totals of the segments below it on the matrix
+// cores, slab by slab, nearest the seed first, a slab filling the other units once.  Behind the
+// chain and behind each slab's totals the second stream runs the chain over the slab's totals,
+// entered by the vector handed on from above, and then the slab's own matrix-vector pass (bound
+// by HBM, or by the vector ALUs on generated Jacobians), which shares the units with the totals
+// of the next slab: 242 + 148 registers per lane, 135 KB + 1 KB of LDS.
 bppsa_status scan_h128_pipelined(int T, int B, int t_min, int S, int nseg, const float* Jt, const float* seed,
                                  float* G, float* g0, float* tot, float* vin, hipStream_t s, SideStream* side,
-                                 int slab, const bppsa_gru_tiles* gen) {
+                                 const bppsa_h128_plan& plan, const bppsa_gru_tiles* gen) {
   constexpr int H = 128;
   const size_t row = (size_t)B * H;
+  const int R = nseg - plan.chain_segments;       // segments R-1 .. 0 lie below the serial chain
+  const int slab = plan.slab;
   std::lock_guard<std::mutex> hold(side->lock);
   hipStream_t s2 = side->stream;
   BPPSA_HIP_TRY(hipEventRecord(side->fork, s));
@@ -222,15 +225,14 @@ bppsa_status scan_h128_pipelined(int T, int B, int t_min, int S, int nseg, const
   // included - goes through the join below: the caller's stream waits for whatever was enqueued
   // on the second stream (and a capturing stream gets its fork joined) before the status returns.
   bppsa_status st = [&]() -> bppsa_status {
-    // seed-side segment: matrix-vector only; its last vector enters segment nseg-2
-    bppsa_status e = launch_apply(T, B, H, t_min, S, nseg - 1, 1, Jt, seed, 1, G, g0,
-                                  vin + (size_t)(nseg - 2) * row, s2, gen);
+    // the serial chain; its last vector enters segment R-1
+    bppsa_status e = bppsa_chain_h128(B, t_min + R * S, T - 1, Jt, seed, G, g0, vin + (size_t)(R - 1) * row, s2, gen);
     if (e != BPPSA_OK) return e;
     int j = 0;
-    for (int hi = nseg - 2; hi >= 0; ++j) {
+    for (int hi = R - 1; hi >= 0; ++j) {
       int lo = hi - slab + 1;
       if (lo <= 1) lo = 0;                        // segment 0 has no total: it rides with the last slab
-      const int rlo = lo < 1 ? 1 : lo;            // totals exist for segments 1 .. nseg-2
+      const int rlo = lo < 1 ? 1 : lo;            // totals exist for segments 1 .. R-1
       if (hi >= rlo) {
         e = launch_reduce(T, B, H, t_min, S, rlo, hi - rlo + 1, Jt, tot, s, gen);
         if (e != BPPSA_OK) return e;
@@ -258,7 +260,8 @@ bppsa_status scan_h128_pipelined(int T, int B, int t_min, int S, int nseg, const
 
 // One level of the recursion; `ws` is the unused tail of the workspace.
 bppsa_status scan_level(int T, int B, int H, const float* Jt, const float* seed,
-                        float* G, float* g0, char* ws, hipStream_t s, const bppsa_gru_tiles* gen = nullptr) {
+                        float* G, float* g0, char* ws, hipStream_t s, const bppsa_gru_tiles* gen = nullptr,
+                        const bppsa_h128_plan* forced = nullptr) {
   const size_t row = (size_t)B * H;
   if (seed != G + (size_t)(T - 1) * row) {
     const long long n = (long long)row;
@@ -280,11 +283,12 @@ bppsa_status scan_level(int T, int B, int H, const float* Jt, const float* seed,
 
   bppsa_status st;
   if (H == 128) {
-    int slab = bppsa_compute_units() / B;             // segments whose totals fill the device once
-    if (slab < 1) slab = 1;
-    if (bppsa_ceil_div(nseg - 1, slab) > kMaxSlabs) slab = bppsa_ceil_div(nseg - 1, kMaxSlabs);
-    SideStream* side = (nseg - 2 >= 2 * slab) ? side_stream() : nullptr;
-    if (side) return scan_h128_pipelined(T, B, t_min, S, nseg, Jt, seed, G, g0, tot, vin, s, side, slab, gen);
+    const bppsa_h128_plan plan = forced ? *forced : bppsa_plan_h128(n, B, bppsa_compute_units(), gen != nullptr);
+    if (plan.chain_segments >= nseg) return bppsa_chain_h128(B, t_min, T - 1, Jt, seed, G, g0, nullptr, s, gen);
+    if (plan.chain_segments >= 1) {
+      SideStream* side = side_stream();
+      if (side) return scan_h128_pipelined(T, B, t_min, S, nseg, Jt, seed, G, g0, tot, vin, s, side, plan, gen);
+    }
   }
   // interior segments 1..nseg-2: matrix-matrix totals (segment 0's total reaches no output)
   st = launch_reduce(T, B, H, t_min, S, 1, nseg - 2, Jt, tot, s, gen);
@@ -302,7 +306,7 @@ bppsa_status scan_level(int T, int B, int H, const float* Jt, const float* seed,
 
 bppsa_status bppsa_scan_generic(int T, int B, int H, const float* Jt, const float* seed,
                                 float* G, float* g0, void* workspace, hipStream_t stream,
-                                const bppsa_gru_tiles* gen) {
-  if (gen && H != 128) return BPPSA_EUNSUPPORTED;
-  return scan_level(T, B, H, Jt, seed, G, g0, static_cast<char*>(workspace), stream, gen);
+                                const bppsa_gru_tiles* gen, const bppsa_h128_plan* plan) {
+  if ((gen || plan) && H != 128) return BPPSA_EUNSUPPORTED;
+  return scan_level(T, B, H, Jt, seed, G, g0, static_cast<char*>(workspace), stream, gen, plan);
 }

@@ -159,11 +159,20 @@ apply_h128_kernel(int T, int B, int t_min, int S, int seg_begin, const float* __
   const float* vsrc = vin_is_seed ? vin + (size_t)b * H : vin + ((size_t)seg * B + b) * H;
   if (tid < H) vs[0][tid] = vsrc[tid];
   v4f pre[GEN ? 1 : kChunks];
+  // Generated form (GRU, Appendix E): Jt v = W_hr^T (a . v) + W_hn^T (c . v) + W_hz^T (e . v) + z . v,
+  // three products with matrices that do not change; no tile is formed.  The thread keeps the
+  // 3 x 16 weight pieces of its places, scales its four entries of v by a, c and e, and the lane
+  // that ends up with a row's sum adds that row's z v.
   GruWeights gw;
   GruCoef cf;
+  // the row whose sum this lane writes if it is a writer (c even): bit 4 of c chose q bit 3,
+  // bit 3 -> q bit 2, bit 2 -> q bit 1, bit 1 -> q bit 0
+  const int row = r + 8 * (((c >> 4) & 1) * 8 + ((c >> 3) & 1) * 4 + ((c >> 2) & 1) * 2 + ((c >> 1) & 1));
+  float zrow = 0.f;
   if (GEN) {
     load_gru_weights(wT, tid, gw);
     cf = load_gru_coef(coef, (size_t)hi * B + b, tid);
+    zrow = coef[((size_t)hi * B + b) * 4 * H + 3 * H + row];
   } else {
     const float* src = Jt + ((size_t)hi * B + b) * HH;
 #pragma unroll
@@ -174,14 +183,32 @@ apply_h128_kernel(int T, int B, int t_min, int S, int seg_begin, const float* __
   for (int t = hi; t >= lo; --t) {
     const v4f x = *reinterpret_cast<const v4f*>(&vs[cur][4 * c]);
     float part[kChunks];
+    float diag = 0.f;
+    if (GEN) {
+      const v4f xa = x * cf.a, xc = x * cf.c, xe = x * cf.e;
+      diag = zrow * vs[cur][row];
 #pragma unroll
-    for (int q = 0; q < kChunks; ++q) {         // row r + 8 q
-      const v4f m = GEN ? gru_piece(gw, cf, tid, q) : pre[q];
-      part[q] = (m[0] * x[0] + m[1] * x[1]) + (m[2] * x[2] + m[3] * x[3]);
+      for (int q = 0; q < kChunks; ++q) {       // row r + 8 q
+        float acc = gw.r[q][0] * xa[0];
+#pragma unroll
+        for (int u = 1; u < 4; ++u) acc += gw.r[q][u] * xa[u];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) acc += gw.n[q][u] * xc[u];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) acc += gw.z[q][u] * xe[u];
+        part[q] = acc;
+      }
+    } else {
+#pragma unroll
+      for (int q = 0; q < kChunks; ++q) {       // row r + 8 q
+        const v4f m = pre[q];
+        part[q] = (m[0] * x[0] + m[1] * x[1]) + (m[2] * x[2] + m[3] * x[3]);
+      }
     }
     if (t - 1 >= lo) {
       if (GEN) {
         cf = load_gru_coef(coef, (size_t)(t - 1) * B + b, tid);
+        zrow = coef[((size_t)(t - 1) * B + b) * 4 * H + 3 * H + row];
       } else {
         const float* src = Jt + ((size_t)(t - 1) * B + b) * HH;
 #pragma unroll
@@ -205,10 +232,7 @@ apply_h128_kernel(int T, int B, int t_min, int S, int seg_begin, const float* __
     BPPSA_HALVE(1, 2)
 #undef BPPSA_HALVE
     // lanes c and c ^ 1 now hold the two halves of row r + 8 * rowsel
-    const float sum = part[0] + __shfl_xor(part[0], 1);
-    // row index: bit 4 of c chose q bit 3, bit 3 -> q bit 2, bit 2 -> q bit 1, bit 1 -> q bit 0
-    const int qsel = ((c >> 4) & 1) * 8 + ((c >> 3) & 1) * 4 + ((c >> 2) & 1) * 2 + ((c >> 1) & 1);
-    const int row = r + 8 * qsel;
+    const float sum = part[0] + __shfl_xor(part[0], 1) + diag;
     float* dst = (t >= 1) ? G + ((size_t)(t - 1) * B + b) * H : g0 + (size_t)b * H;
     if ((c & 1) == 0) {
       vs[cur ^ 1][row] = sum;
@@ -216,6 +240,171 @@ apply_h128_kernel(int T, int B, int t_min, int S, int seg_begin, const float* __
     }
     __syncthreads();
     cur ^= 1;
+  }
+  if (v_out && tid < H) v_out[(size_t)b * H + tid] = vs[cur][tid];
+}
+
+// The seed-side stretch of a long chain: v <- Jt[t] v for t = hi..lo with one workgroup of 1024
+// threads per sample, writing g[t] = v to G[t-1] (g0 when t == 0) and the last vector to v_out.
+// Nothing here is parallel over t, so a step must be short: thread (r, c) = (tid / 32, tid % 32)
+// holds columns 4c..4c+3 of rows r, r+32, r+64, r+96 (four 16-byte pieces per tile) and the 32
+// partial sums of a row meet in six exchanges.  Sixteen waves fill a compute unit's registers:
+// the workgroup has the unit to itself.
+constexpr int kChainThreads = 1024;
+constexpr int kChainPieces = HH / 4 / kChainThreads;   // 4
+
+// partial sums part[q] of rows r + 32 q over the thread's four columns -> the row sum, held by
+// the eight lanes c with the same c / 8; returns the row and leaves the sum in `sum`
+__device__ __forceinline__ int chain_row_sum(float (&part)[kChainPieces], int r, int c, float& sum) {
+  // halving exchange: lane bit 4 keeps the rows with q bit 1 equal to it, lane bit 3 those with
+  // q bit 0; the remaining eight lanes of a row then add up
+  {
+    const bool upper = (c & 16) != 0;
+    const float m0 = upper ? part[2] : part[0], s0 = upper ? part[0] : part[2];
+    const float m1 = upper ? part[3] : part[1], s1 = upper ? part[1] : part[3];
+    part[0] = m0 + __shfl_xor(s0, 16);
+    part[1] = m1 + __shfl_xor(s1, 16);
+  }
+  {
+    const bool upper = (c & 8) != 0;
+    const float m0 = upper ? part[1] : part[0], s0 = upper ? part[0] : part[1];
+    part[0] = m0 + __shfl_xor(s0, 8);
+  }
+  sum = part[0];
+  sum += __shfl_xor(sum, 4);
+  sum += __shfl_xor(sum, 2);
+  sum += __shfl_xor(sum, 1);
+  return r + 32 * (((c >> 4) & 1) * 2 + ((c >> 3) & 1));
+}
+
+// Stored Jacobians: kChainDepth tiles are in flight in registers.  (A compute unit draws about
+// 50 GB/s from memory however many requests it has outstanding, so a step of this form takes
+// 1.3 us: six tiles in flight are more than that needs.)
+constexpr int kChainDepth = 6;
+
+__global__ void __launch_bounds__(kChainThreads)
+chain_h128_kernel(int B, int lo, int hi, const float* __restrict__ Jt, const float* __restrict__ seed,
+                  float* __restrict__ G, float* __restrict__ g0, float* __restrict__ v_out) {
+  __shared__ __attribute__((aligned(16))) float vs[2][H];
+  const int tid = threadIdx.x;
+  const int c = tid & 31, r = tid >> 5;
+  const int b = blockIdx.x;
+  if (tid < H) vs[0][tid] = seed[(size_t)b * H + tid];
+  v4f pre[kChainDepth][kChainPieces];
+  auto request = [&](int slot, int t) {          // t below lo: a tile nobody uses, no branch
+    const v4f* src = reinterpret_cast<const v4f*>(Jt + ((size_t)max(t, lo) * B + b) * HH);
+#pragma unroll
+    for (int q = 0; q < kChainPieces; ++q) pre[slot][q] = src[tid + q * kChainThreads];
+  };
+#pragma unroll
+  for (int k = 0; k < kChainDepth; ++k) request(k, hi - k);
+  __syncthreads();
+  int cur = 0;
+  for (int t0 = hi; t0 >= lo; t0 -= kChainDepth) {
+#pragma unroll
+    for (int k = 0; k < kChainDepth; ++k) {
+      const int t = t0 - k;
+      if (t < lo) break;                          // uniform
+      const v4f x = *reinterpret_cast<const v4f*>(&vs[cur][4 * c]);
+      float part[kChainPieces];
+#pragma unroll
+      for (int q = 0; q < kChainPieces; ++q) {    // row r + 32 q
+        const v4f m = pre[k][q];
+        part[q] = (m[0] * x[0] + m[1] * x[1]) + (m[2] * x[2] + m[3] * x[3]);
+      }
+      request(k, t - kChainDepth);
+      float sum;
+      const int row = chain_row_sum(part, r, c, sum);
+      float* dst = (t >= 1) ? G + ((size_t)(t - 1) * B + b) * H : g0 + (size_t)b * H;
+      if ((c & 7) == 0) {
+        vs[cur ^ 1][row] = sum;
+        dst[row] = sum;
+      }
+      __syncthreads();
+      cur ^= 1;
+    }
+  }
+  if (v_out && tid < H) v_out[(size_t)b * H + tid] = vs[cur][tid];
+}
+
+// Generated Jacobians (GRU, Appendix E).  With Jt = W_hr^T diag(a) + W_hn^T diag(c) + W_hz^T diag(e)
+// + diag(z), a step is Jt v = W_hr^T (a . v) + W_hn^T (c . v) + W_hz^T (e . v) + z . v: three products
+// with matrices that do not change, so no tile is formed at all.  The thread keeps the 3 x 4 weight
+// pieces of its places in registers, scales its four entries of v by a, c and e, and spends three
+// multiply-adds per entry of a tile.  The coefficient vectors of kChainBlock steps at a time (2 KB
+// per step) go through LDS, the next block already in flight in registers while one is in use.
+constexpr int kChainBlock = 8;
+
+__global__ void __launch_bounds__(kChainThreads)
+chain_h128_gen_kernel(int B, int lo, int hi, const float* __restrict__ seed, float* __restrict__ G,
+                      float* __restrict__ g0, float* __restrict__ v_out, const float* __restrict__ coef,
+                      const float* __restrict__ wT) {
+  __shared__ __attribute__((aligned(16))) float vs[2][H];
+  __shared__ __attribute__((aligned(16))) float cfs[2][kChainBlock][4 * H];
+  const int tid = threadIdx.x;
+  const int c = tid & 31, r = tid >> 5;
+  const int b = blockIdx.x;
+  if (tid < H) vs[0][tid] = seed[(size_t)b * H + tid];
+  v4f wr[kChainPieces], wn[kChainPieces], wz[kChainPieces];
+#pragma unroll
+  for (int q = 0; q < kChainPieces; ++q) {
+    const int e = tid + q * kChainThreads;
+    wr[q] = reinterpret_cast<const v4f*>(wT)[e];
+    wn[q] = reinterpret_cast<const v4f*>(wT + HH)[e];
+    wz[q] = reinterpret_cast<const v4f*>(wT + 2 * HH)[e];
+  }
+  // the block of steps t0 .. t0 - 7: thread (j, p) = (tid / 128, tid % 128) moves piece p of step
+  // t0 - j (clamped to lo: rows nobody uses)
+  const int bj = tid >> 7, bp = tid & 127;
+  v4f in;
+  auto request = [&](int t0) {
+    in = reinterpret_cast<const v4f*>(coef + ((size_t)max(t0 - bj, lo) * B + b) * 4 * H)[bp];
+  };
+  auto deposit = [&](int buf) { reinterpret_cast<v4f*>(&cfs[buf][bj][0])[bp] = in; };
+  request(hi);
+  deposit(0);
+  request(hi - kChainBlock);
+  __syncthreads();
+  // the row this lane writes if it is one of the writers (c % 8 == 0)
+  const int row = r + 32 * (((c >> 4) & 1) * 2 + ((c >> 3) & 1));
+  int cur = 0, buf = 0;
+  for (int t0 = hi; t0 >= lo; t0 -= kChainBlock) {
+    for (int j = 0; j < kChainBlock; ++j) {
+      const int t = t0 - j;
+      if (t < lo) break;                          // uniform
+      const v4f x = *reinterpret_cast<const v4f*>(&vs[cur][4 * c]);
+      const v4f* f = reinterpret_cast<const v4f*>(&cfs[buf][j][0]) + c;
+      const v4f xa = x * f[0], xc = x * f[H / 4], xe = x * f[2 * (H / 4)];
+      const float diag = cfs[buf][j][3 * H + row] * vs[cur][row];
+      float part[kChainPieces];
+#pragma unroll
+      for (int q = 0; q < kChainPieces; ++q) {    // row r + 32 q
+        float acc = wr[q][0] * xa[0];
+#pragma unroll
+        for (int u = 1; u < 4; ++u) acc += wr[q][u] * xa[u];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) acc += wn[q][u] * xc[u];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) acc += wz[q][u] * xe[u];
+        part[q] = acc;
+      }
+      float sum;
+      chain_row_sum(part, r, c, sum);
+      sum += diag;
+      float* dst = (t >= 1) ? G + ((size_t)(t - 1) * B + b) * H : g0 + (size_t)b * H;
+      if ((c & 7) == 0) {
+        vs[cur ^ 1][row] = sum;
+        dst[row] = sum;
+      }
+      __syncthreads();
+      cur ^= 1;
+    }
+    // the other buffer was last read in the block before this one, behind many barriers; the
+    // barrier below puts its new contents in front of the next block's reads
+    deposit(buf ^ 1);
+    request(t0 - 2 * kChainBlock);
+    __syncthreads();
+    buf ^= 1;
   }
   if (v_out && tid < H) v_out[(size_t)b * H + tid] = vs[cur][tid];
 }
@@ -246,6 +435,17 @@ bppsa_status bppsa_apply_h128(int T, int B, int t_min, int S, int seg_begin, int
   else
     apply_h128_kernel<false><<<dim3(seg_count, B), kThreads, 0, s>>>(T, B, t_min, S, seg_begin, Jt, vin,
                                                                      vin_is_seed, G, g0, v_out, nullptr, nullptr);
+  BPPSA_CHECK_LAUNCH();
+  return BPPSA_OK;
+}
+
+bppsa_status bppsa_chain_h128(int B, int lo, int hi, const float* Jt, const float* seed, float* G, float* g0,
+                              float* v_out, hipStream_t s, const bppsa_gru_tiles* gen) {
+  if (hi < lo) return BPPSA_OK;
+  if (gen)
+    chain_h128_gen_kernel<<<B, kChainThreads, 0, s>>>(B, lo, hi, seed, G, g0, v_out, gen->coef, gen->wT);
+  else
+    chain_h128_kernel<<<B, kChainThreads, 0, s>>>(B, lo, hi, Jt, seed, G, g0, v_out);
   BPPSA_CHECK_LAUNCH();
   return BPPSA_OK;
 }

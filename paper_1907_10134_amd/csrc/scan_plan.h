@@ -59,9 +59,76 @@ struct bppsa_gru_tiles {
   const float* wT;
 };
 
+// ---- schedule of a long H = 128 chain ---------------------------------------------------
+// The chain is cut into segments of bppsa_generic_segment steps, counted from the far end (the
+// last one, nearest the seed, may be shorter).  At this size a step of the matrix-matrix side
+// costs 128 times the arithmetic of a matrix-vector step, so the hybrid schedule of Section 5.3
+// is taken one step further: the `chain_segments` segments nearest the seed are walked by one
+// serial matrix-vector chain per sample, on a compute unit of its own, while the totals of the
+// other segments are formed on the matrix cores in slabs of `slab` segments; behind the chain and
+// each slab's totals come the slab's matrix-vector passes.  chain_segments = 0: the two-level
+// form without the serial chain (used when the batch alone fills the device); chain_segments =
+// all segments: no matrix-matrix product at all.
+#define BPPSA_H128_MAX_SLABS 32
+struct bppsa_h128_plan {
+  int chain_segments;
+  int slab;
+  int slabs;
+  double model_us;      // the estimate the choice was made on
+};
+
+// The schedule of the cost model below, or the one the caller forces (chain_segments >= 0).
+// Times in microseconds, measured on MI355X: a step of the serial chain (1024 threads, one
+// compute unit per sample; bound by what one unit draws from memory, or by its vector ALUs when
+// the Jacobians are generated), a step of a segment's running product on the matrix cores with
+// the device full, a step of the chain over a slab's totals, and the matrix-vector pass of a slab
+// (HBM-bound on stored Jacobians, ALU-bound on generated ones).
+static inline bppsa_h128_plan bppsa_plan_h128(int n, int B, int cus, bool generated, int force_chain = -1,
+                                              int force_slab = 0) {
+  const int S = bppsa_generic_segment(128);
+  const int nseg = bppsa_ceil_div(n, S);
+  bppsa_h128_plan best = {0, 0, 0, 0.0};
+  if (cus < 2 * B || nseg < 2) return best;
+  const double chain_step = generated ? 0.97 : 1.38, product_step = 9.6, totals_step = 1.6;
+  const int top_steps = n - (nseg - 1) * S;
+  const int free_units = cus - B;                       // the serial chains keep B units to themselves
+  double best_us = 1e300;
+  const int k_lo = force_chain >= 0 ? (force_chain < 1 ? 1 : force_chain > nseg ? nseg : force_chain) : 1;
+  const int k_hi = force_chain >= 0 ? k_lo : nseg;
+  for (int K = k_lo; K <= k_hi; ++K) {
+    double cur = (double)(top_steps + (K - 1) * S) * chain_step;
+    int slab = 0, slabs = 0;
+    if (K < nseg) {
+      const int R = nseg - K;                           // segments R-1 .. 0 lie below the chain
+      slab = force_slab > 0 ? force_slab : free_units / B;
+      if (slab < 1) slab = 1;
+      if (bppsa_ceil_div(R, slab) > BPPSA_H128_MAX_SLABS) slab = bppsa_ceil_div(R, BPPSA_H128_MAX_SLABS);
+      double reduce_end = 0.0;
+      for (int hi = R - 1; hi >= 0;) {                  // the same walk as the launcher's
+        int lo = hi - slab + 1;
+        if (lo <= 1) lo = 0;
+        const int rlo = lo < 1 ? 1 : lo;
+        const int totals = hi >= rlo ? hi - rlo + 1 : 0, segs = hi - lo + 1;
+        if (totals > 0) reduce_end += (S - 1) * product_step * bppsa_ceil_div(totals * B, free_units);
+        const double apply_us = generated ? S * 1.4 * bppsa_ceil_div(segs * B, cus)
+                                          : (double)segs * B * S * (128.0 * 128.0 * 4.0) / 4.3e6;
+        cur = (cur > reduce_end ? cur : reduce_end) + totals * totals_step + apply_us;
+        ++slabs;
+        hi = lo - 1;
+      }
+    }
+    if (cur < best_us) {
+      best_us = cur;
+      best = {K, slab, slabs, cur};
+    }
+  }
+  return best;
+}
+
+// plan (H = 128 only): null = chosen by bppsa_plan_h128; otherwise the schedule to use
 bppsa_status bppsa_scan_generic(int T, int B, int H, const float* Jt, const float* seed,
                                 float* G, float* g0, void* workspace, hipStream_t stream,
-                                const bppsa_gru_tiles* gen = nullptr);
+                                const bppsa_gru_tiles* gen = nullptr, const bppsa_h128_plan* plan = nullptr);
 
 // ---- matrix-core kernels for H = 128 (used by the generic scan's reduce and apply steps) ----
 bppsa_status bppsa_reduce_h128(int T, int B, int t_min, int S, int seg_begin, int seg_count,
@@ -71,6 +138,11 @@ bppsa_status bppsa_reduce_h128_gen(int T, int B, int t_min, int S, int seg_begin
                                    hipStream_t s, const bppsa_gru_tiles* gen);
 bppsa_status bppsa_apply_h128(int T, int B, int t_min, int S, int seg_begin, int seg_count,
                               const float* Jt, const float* vin, int vin_is_seed, float* G, float* g0,
+                              float* v_out, hipStream_t s, const bppsa_gru_tiles* gen = nullptr);
+
+// One serial chain per sample over steps hi..lo (seeded by seed [B, H]); g[t] goes to G[t-1] (g0 for
+// t = 0, which must not be null if lo = 0), the last vector to v_out [B, H] if not null.
+bppsa_status bppsa_chain_h128(int B, int lo, int hi, const float* Jt, const float* seed, float* G, float* g0,
                               float* v_out, hipStream_t s, const bppsa_gru_tiles* gen = nullptr);
 
 // coef and wT of bppsa_gru_tiles from the hidden states, inputs and weights (gates recomputed).
