@@ -300,8 +300,8 @@ def gru_workload(bp, workloads, steps):
     return {"workload": "gru_H128_I1_T4096_B16 (configs[3])", **{k: round(v, 4) for k, v in parts.items()},
             "fused_scan_ms": round(fused_ms, 4),
             "fused_vs_build_plus_scan": round((parts["build_jacobians_ms"] + parts["scan_ms"]) / fused_ms, 3),
-            "schedule": {k: sched[k] for k in ("segment_steps", "chain_steps", "slab_segments", "slabs")},
-            "fused_schedule": {k: fsched[k] for k in ("segment_steps", "chain_steps", "slab_segments", "slabs",
+            "schedule": {k: sched[k] for k in ("segment_steps", "chain_steps", "slab_segments", "slabs", "last_slab_steps")},
+            "fused_schedule": {k: fsched[k] for k in ("segment_steps", "chain_steps", "slab_segments", "slabs", "last_slab_steps",
                                                       "matrix_products")},
             "scan_matrix_products": mm, "scan_flop": flop, "scan_tflops": round(tf, 2),
             "frac_of_fp32_mfma_peak": round(tf / 157.3, 4),

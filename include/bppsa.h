@@ -479,7 +479,9 @@ bppsa_status bppsa_scan_h20_diag(int T, int B, const float* Jt, const float* see
  * are walked by one serial matrix-vector chain per sample while the totals of the remaining
  * segments are formed with matrix-matrix products, `slab_segments` segments at a time
  * (`slabs` slabs; 0 when no slab is formed, or when the batch alone fills the device and the
- * totals of all segments are formed at once and scanned recursively).  `matrix_products` counts
+ * totals of all segments are formed at once and scanned recursively).  The slab farthest from the
+ * seed is cut into segments of `last_slab_steps` steps (shorter than `segment_steps` when it
+ * would otherwise fill less than half of the device; 0 when there is no slab).  `matrix_products` counts
  * the H x H matrix-matrix products of the call, `model_us` is the estimate the choice was made
  * on (0 where no choice is made).  Host only, no device work.
  * Errors: BPPSA_EINVAL (T or B below 1, out NULL).
@@ -490,6 +492,7 @@ typedef struct {
   int chain_steps;
   int slab_segments;
   int slabs;
+  int last_slab_steps;
   int64_t matrix_products;
   double model_us;
 } bppsa_h128_schedule;
@@ -503,13 +506,16 @@ bppsa_status bppsa_scan_h128_schedule(int T, int B, int want_g0, int generated, 
  *                    the serial chain (totals of all interior segments, scanned recursively).
  *   slab_segments  : segments per slab of totals; 0 = as many as fill the compute units that the
  *                    serial chains leave free.  Raised if more than 32 slabs would result.
- * Errors: those of bppsa_scan; BPPSA_EUNSUPPORTED if chain_segments > 0 and the device has fewer
- * than 2 B compute units (the serial chains take one each).
+ *   last_slab_steps: 64, 32 or 16 = segment length inside the slab farthest from the seed; 0 =
+ *                    whichever the cost model prefers.
+ * Errors: those of bppsa_scan; BPPSA_EINVAL for another last_slab_steps; BPPSA_EUNSUPPORTED if
+ * chain_segments > 0 and the device has fewer than 2 B compute units (the serial chains take one
+ * each); BPPSA_ESHAPE if the last slab cut that fine would have more than 32 segments.
  */
 bppsa_status bppsa_scan_h128_diag(int T, int B, const float* Jt, const float* seed,
                                   float* G, float* g0,
                                   void* workspace, size_t workspace_bytes, void* stream,
-                                  int chain_segments, int slab_segments);
+                                  int chain_segments, int slab_segments, int last_slab_steps);
 
 /*
  * Plain streaming copy dst[i] = src[i] of n fp32 values (n a multiple of 4,

@@ -47,7 +47,7 @@ def _load(path=_LIB_PATH):
     lib.bppsa_scan_h20_diag.restype = c_int
     lib.bppsa_scan_h20_diag.argtypes = [c_int] * 2 + [c_void_p] * 5 + [c_size_t, c_void_p, c_int, c_int, c_void_p]
     lib.bppsa_scan_h128_diag.restype = c_int
-    lib.bppsa_scan_h128_diag.argtypes = [c_int] * 2 + [c_void_p] * 5 + [c_size_t, c_void_p, c_int, c_int]
+    lib.bppsa_scan_h128_diag.argtypes = [c_int] * 2 + [c_void_p] * 5 + [c_size_t, c_void_p, c_int, c_int, c_int]
     lib.bppsa_scan_h128_schedule.restype = c_int
     lib.bppsa_scan_h128_schedule.argtypes = [c_int] * 4 + [ctypes.POINTER(H128Schedule)]
     lib.bppsa_scan_static.restype = c_int
@@ -141,7 +141,8 @@ class CsrDesc(ctypes.Structure):
 
 class H128Schedule(ctypes.Structure):
     """bppsa_h128_schedule."""
-    _fields_ = [(k, ctypes.c_int32) for k in ("segment_steps", "segments", "chain_steps", "slab_segments", "slabs")] + \
+    _fields_ = [(k, ctypes.c_int32) for k in ("segment_steps", "segments", "chain_steps", "slab_segments", "slabs",
+                                              "last_slab_steps")] + \
                [("matrix_products", ctypes.c_int64), ("model_us", ctypes.c_double)]
 
 
@@ -291,9 +292,10 @@ def scan_h20_diag(Jt, seed, G=None, g0=None, workspace=None, stream=None, absent
     return G
 
 
-def scan_h128_diag(Jt, seed, G=None, g0=None, workspace=None, stream=None, chain_segments=0, slab_segments=0):
+def scan_h128_diag(Jt, seed, G=None, g0=None, workspace=None, stream=None, chain_segments=0, slab_segments=0,
+                   last_slab_steps=0):
     """bppsa_scan_h128_diag: the H = 128 scan with a forced schedule (segments walked by the serial
-    chain, segments per slab of totals)."""
+    chain, segments per slab of totals, segment length inside the last slab)."""
     T, B, H, _ = Jt.shape
     if G is None:
         G = torch.empty((T, B, H), dtype=torch.float32, device=Jt.device)
@@ -301,7 +303,7 @@ def scan_h128_diag(Jt, seed, G=None, g0=None, workspace=None, stream=None, chain
         workspace = _workspace(scan_workspace_bytes(T, B, H), Jt.device, stream)
     _check(_lib.bppsa_scan_h128_diag(T, B, _ptr(Jt), _ptr(seed), _ptr(G), _ptr(g0), workspace.data_ptr(),
                                      workspace.numel() * workspace.element_size(), _stream(stream),
-                                     int(chain_segments), int(slab_segments)),
+                                     int(chain_segments), int(slab_segments), int(last_slab_steps)),
            "bppsa_scan_h128_diag")
     return G
 

@@ -33,6 +33,7 @@ size_t scan_ws_bytes(int T, int B, int H) {
   const size_t a = bppsa_generic_scan_ws(T, B, H, 0);
   const size_t b = bppsa_generic_scan_ws(T, B, H, 1);
   size_t need = (a > b ? a : b) + 256;
+  if (H == 128) need += bppsa_h128_fine_ws(T, B, 1);
   if (H == 20) {
     const size_t c = bppsa_h20_scan_ws(T, B);
     if (c > need) need = c;
@@ -116,7 +117,20 @@ extern "C" bppsa_status bppsa_scan_h128_schedule(int T, int B, int want_g0, int 
   if (plan.chain_segments < nseg) {
     out->slab_segments = plan.slab;
     out->slabs = plan.slabs;
-    out->matrix_products = (long long)(nseg - plan.chain_segments - 1) * (S - 1) * B;
+    out->last_slab_steps = plan.last_steps;
+    // every segment below the chain but the farthest has a total; where the last slab is cut
+    // finer, each of its segments of S steps becomes S / last_steps segments
+    const int R = nseg - plan.chain_segments;
+    long long products = 0;
+    for (int hi = R - 1; hi >= 0;) {
+      const bppsa_h128_slab sl = bppsa_h128_next_slab(hi, plan.slab);
+      if (sl.lo == 0 && plan.last_steps < S)
+        products += (long long)((sl.hi + 1) * (S / plan.last_steps) - 1) * (plan.last_steps - 1);
+      else if (sl.hi >= sl.rlo)
+        products += (long long)(sl.hi - sl.rlo + 1) * (S - 1);
+      hi = sl.lo - 1;
+    }
+    out->matrix_products = products * B;
   }
   out->model_us = plan.model_us;
   return BPPSA_OK;
@@ -124,8 +138,10 @@ extern "C" bppsa_status bppsa_scan_h128_schedule(int T, int B, int want_g0, int 
 
 extern "C" bppsa_status bppsa_scan_h128_diag(int T, int B, const float* Jt, const float* seed, float* G, float* g0,
                                              void* workspace, size_t workspace_bytes, void* stream,
-                                             int chain_segments, int slab_segments) {
+                                             int chain_segments, int slab_segments, int last_slab_steps) {
   if (T < 1 || B < 1 || chain_segments < 0 || slab_segments < 0) return BPPSA_EINVAL;
+  if (last_slab_steps != 0 && last_slab_steps != 16 && last_slab_steps != 32 && last_slab_steps != 64)
+    return BPPSA_EINVAL;
   if (!Jt || !seed || !G) return BPPSA_EINVAL;
   if (bppsa_mul_overflows(T, B, 128, 128)) return BPPSA_EOVERFLOW;
   if (B > 65535) return BPPSA_ESHAPE;
@@ -133,11 +149,12 @@ extern "C" bppsa_status bppsa_scan_h128_diag(int T, int B, const float* Jt, cons
   if (need > 256 && (!workspace || workspace_bytes < need)) return BPPSA_EWORKSPACE;
   if (workspace && ((uintptr_t)workspace & 255)) return BPPSA_EINVAL;
   const int n = T - (g0 ? 0 : 1);
-  bppsa_h128_plan plan = {0, 0, 0, 0.0};
+  bppsa_h128_plan plan = {0, 0, 0, bppsa_generic_segment(128), 0.0};
   if (chain_segments > 0) {
     // the serial chain needs a compute unit per sample beside the matrix-core work
     if (bppsa_compute_units() < 2 * B) return BPPSA_EUNSUPPORTED;
-    plan = bppsa_plan_h128(n, B, bppsa_compute_units(), false, chain_segments, slab_segments);
+    plan = bppsa_plan_h128(n, B, bppsa_compute_units(), false, chain_segments, slab_segments, last_slab_steps);
+    if (plan.chain_segments == 0) return BPPSA_ESHAPE;   // no schedule of that kind fits these sizes
   }
   return bppsa_scan_generic(T, B, 128, Jt, seed, G, g0, workspace, (hipStream_t)stream, nullptr, &plan);
 }

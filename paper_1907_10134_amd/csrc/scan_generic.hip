@@ -211,12 +211,12 @@ SideStream* side_stream() {
 // by HBM, or by the vector ALUs on generated Jacobians), which shares the units with the totals
 // of the next slab: 242 + 148 registers per lane, 135 KB + 1 KB of LDS.
 bppsa_status scan_h128_pipelined(int T, int B, int t_min, int S, int nseg, const float* Jt, const float* seed,
-                                 float* G, float* g0, float* tot, float* vin, hipStream_t s, SideStream* side,
-                                 const bppsa_h128_plan& plan, const bppsa_gru_tiles* gen) {
+                                 float* G, float* g0, float* tot, float* vin, float* fine_tot, float* fine_vin,
+                                 hipStream_t s, SideStream* side, const bppsa_h128_plan& plan,
+                                 const bppsa_gru_tiles* gen) {
   constexpr int H = 128;
   const size_t row = (size_t)B * H;
   const int R = nseg - plan.chain_segments;       // segments R-1 .. 0 lie below the serial chain
-  const int slab = plan.slab;
   std::lock_guard<std::mutex> hold(side->lock);
   hipStream_t s2 = side->stream;
   BPPSA_HIP_TRY(hipEventRecord(side->fork, s));
@@ -230,25 +230,45 @@ bppsa_status scan_h128_pipelined(int T, int B, int t_min, int S, int nseg, const
     if (e != BPPSA_OK) return e;
     int j = 0;
     for (int hi = R - 1; hi >= 0; ++j) {
-      int lo = hi - slab + 1;
-      if (lo <= 1) lo = 0;                        // segment 0 has no total: it rides with the last slab
-      const int rlo = lo < 1 ? 1 : lo;            // totals exist for segments 1 .. R-1
-      if (hi >= rlo) {
-        e = launch_reduce(T, B, H, t_min, S, rlo, hi - rlo + 1, Jt, tot, s, gen);
+      if (j >= kMaxSlabs) return BPPSA_EINVAL;
+      const bppsa_h128_slab sl = bppsa_h128_next_slab(hi, plan.slab);
+      // this slab's own view of its stretch of the chain: segments [lo, top] of `steps` steps counted
+      // from t_min, totals and incoming vectors in `stot` and `svin` (indexed by segment), the
+      // vector entering segment `top` already in svin[top]
+      int steps = S, lo = sl.lo, rlo = sl.rlo, top = sl.hi;
+      float *stot = tot, *svin = vin;
+      if (sl.lo == 0 && plan.last_steps < S) {
+        // the slab farthest from the seed, cut into shorter segments with room of their own
+        const int f = S / plan.last_steps;
+        steps = plan.last_steps;
+        top = (sl.hi + 1) * f - 1;
+        rlo = 1;
+        stot = fine_tot;
+        svin = fine_vin;
+        if (top + 1 > BPPSA_H128_FINE_SEGMENTS) return BPPSA_EINVAL;
+      }
+      if (top >= rlo) {
+        e = launch_reduce(t_min + (top + 1) * steps, B, H, t_min, steps, rlo, top - rlo + 1, Jt, stot, s, gen);
         if (e != BPPSA_OK) return e;
       }
       BPPSA_HIP_TRY(hipEventRecord(side->slab[j], s));
       BPPSA_HIP_TRY(hipStreamWaitEvent(s2, side->slab[j], 0));
-      if (hi >= rlo) {
-        // vin[seg-1] = tot[seg] vin[seg] for seg = hi .. rlo: the totals as a chain of hi-rlo+1
-        // steps, entered by vin[hi]; also gives the next slab its entering vector
-        e = launch_apply(hi + 1, B, H, rlo, hi - rlo + 1, 0, 1, tot, vin + (size_t)hi * row, 1, vin, nullptr,
+      if (svin != vin) {
+        copy_rows_kernel<<<(int)((row + 255) / 256), 256, 0, s2>>>((long long)row, vin + (size_t)sl.hi * row,
+                                                                   svin + (size_t)top * row);
+        BPPSA_CHECK_LAUNCH();
+      }
+      if (top >= rlo) {
+        // svin[seg-1] = stot[seg] svin[seg] for seg = top .. rlo: the totals as a chain of
+        // top-rlo+1 steps, entered by svin[top]; also gives the next slab its entering vector
+        e = launch_apply(top + 1, B, H, rlo, top - rlo + 1, 0, 1, stot, svin + (size_t)top * row, 1, svin, nullptr,
                          nullptr, s2);
         if (e != BPPSA_OK) return e;
       }
-      e = launch_apply(T, B, H, t_min, S, lo, hi - lo + 1, Jt, vin, 0, G, g0, nullptr, s2, gen);
+      e = launch_apply(svin == vin ? T : t_min + (top + 1) * steps, B, H, t_min, steps, lo, top - lo + 1, Jt, svin, 0, G,
+                       g0, nullptr, s2, gen);
       if (e != BPPSA_OK) return e;
-      hi = lo - 1;
+      hi = sl.lo - 1;
     }
     return BPPSA_OK;
   }();
@@ -287,7 +307,13 @@ bppsa_status scan_level(int T, int B, int H, const float* Jt, const float* seed,
     if (plan.chain_segments >= nseg) return bppsa_chain_h128(B, t_min, T - 1, Jt, seed, G, g0, nullptr, s, gen);
     if (plan.chain_segments >= 1) {
       SideStream* side = side_stream();
-      if (side) return scan_h128_pipelined(T, B, t_min, S, nseg, Jt, seed, G, g0, tot, vin, s, side, plan, gen);
+      if (side) {
+        float* fine_tot = reinterpret_cast<float*>(ws);
+        float* fine_vin = reinterpret_cast<float*>(
+            ws + bppsa_align_up((size_t)BPPSA_H128_FINE_SEGMENTS * row * H * sizeof(float), 256));
+        return scan_h128_pipelined(T, B, t_min, S, nseg, Jt, seed, G, g0, tot, vin, fine_tot, fine_vin, s, side, plan,
+                                   gen);
+      }
     }
   }
   // interior segments 1..nseg-2: matrix-matrix totals (segment 0's total reaches no output)

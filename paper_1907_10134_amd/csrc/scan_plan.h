@@ -27,6 +27,15 @@ static inline size_t bppsa_generic_scan_ws(int T, int B, int H, int want_g0) {
   return total;
 }
 
+// H = 128: the slab of segments farthest from the seed may be cut into shorter segments (see
+// bppsa_h128_plan); their totals and incoming vectors, at most this many, have room of their own.
+#define BPPSA_H128_FINE_SEGMENTS 32
+static inline size_t bppsa_h128_fine_ws(int T, int B, int want_g0) {
+  if (T - (want_g0 ? 0 : 1) <= bppsa_generic_segment(128)) return 0;
+  return bppsa_align_up((size_t)BPPSA_H128_FINE_SEGMENTS * B * 128 * 128 * sizeof(float), 256) +
+         bppsa_align_up((size_t)BPPSA_H128_FINE_SEGMENTS * B * 128 * sizeof(float), 256);
+}
+
 // ---- single-pass path for H = 20 --------------------------------------------------------
 #define BPPSA_H20_SEGMENT 32
 #define BPPSA_H20_AGG_STRIDE 416   /* floats: a 20x20 total padded to 13 cache lines */
@@ -74,54 +83,87 @@ struct bppsa_h128_plan {
   int chain_segments;
   int slab;
   int slabs;
+  int last_steps;       // segment length inside the slab farthest from the seed (S, S/2 or S/4): a
+                        // slab that would fill less than half of the device is cut finer, which
+                        // shortens its products in proportion
   double model_us;      // the estimate the choice was made on
 };
 
-// The schedule of the cost model below, or the one the caller forces (chain_segments >= 0).
-// Times in microseconds, measured on MI355X: a step of the serial chain (1024 threads, one
-// compute unit per sample; bound by what one unit draws from memory, or by its vector ALUs when
-// the Jacobians are generated), a step of a segment's running product on the matrix cores with
-// the device full, a step of the chain over a slab's totals, and the matrix-vector pass of a slab
-// (HBM-bound on stored Jacobians, ALU-bound on generated ones).
+// One slab of the walk below the serial chain, shared by the cost model and the launcher:
+// segments [lo, hi] of S steps, totals for [rlo, hi].
+struct bppsa_h128_slab {
+  int lo, hi, rlo;
+};
+static inline bppsa_h128_slab bppsa_h128_next_slab(int hi, int slab) {
+  int lo = hi - slab + 1;
+  if (lo <= 1) lo = 0;                        // segment 0 has no total: it rides with the last slab
+  return bppsa_h128_slab{lo, hi, lo < 1 ? 1 : lo};
+}
+
+// The schedule of the cost model below, or the one the caller forces (force_chain >= 0; force_slab
+// and force_last 0 = not forced).  Times in microseconds, measured on MI355X: a step of the serial
+// chain (1024 threads, one compute unit per sample; bound by what one unit draws from memory, or
+// by its vector ALUs when the Jacobians are generated), a step of a segment's running product on
+// the matrix cores with the other units full, a step of the chain over a slab's totals, and the
+// matrix-vector pass of a slab (HBM-bound on stored Jacobians, ALU-bound on generated ones).
 static inline bppsa_h128_plan bppsa_plan_h128(int n, int B, int cus, bool generated, int force_chain = -1,
-                                              int force_slab = 0) {
+                                              int force_slab = 0, int force_last = 0) {
   const int S = bppsa_generic_segment(128);
   const int nseg = bppsa_ceil_div(n, S);
-  bppsa_h128_plan best = {0, 0, 0, 0.0};
+  bppsa_h128_plan best = {0, 0, 0, S, 0.0};
   if (cus < 2 * B || nseg < 2) return best;
-  const double chain_step = generated ? 0.97 : 1.38, product_step = 9.6, totals_step = 1.6;
+  const double chain_step = generated ? 0.80 : 1.40, product_step = generated ? 8.8 : 8.3, totals_step = 1.8;
   const int top_steps = n - (nseg - 1) * S;
   const int free_units = cus - B;                       // the serial chains keep B units to themselves
   double best_us = 1e300;
   const int k_lo = force_chain >= 0 ? (force_chain < 1 ? 1 : force_chain > nseg ? nseg : force_chain) : 1;
   const int k_hi = force_chain >= 0 ? k_lo : nseg;
-  for (int K = k_lo; K <= k_hi; ++K) {
-    double cur = (double)(top_steps + (K - 1) * S) * chain_step;
-    int slab = 0, slabs = 0;
-    if (K < nseg) {
-      const int R = nseg - K;                           // segments R-1 .. 0 lie below the chain
-      slab = force_slab > 0 ? force_slab : free_units / B;
-      if (slab < 1) slab = 1;
-      if (bppsa_ceil_div(R, slab) > BPPSA_H128_MAX_SLABS) slab = bppsa_ceil_div(R, BPPSA_H128_MAX_SLABS);
-      double reduce_end = 0.0;
-      for (int hi = R - 1; hi >= 0;) {                  // the same walk as the launcher's
-        int lo = hi - slab + 1;
-        if (lo <= 1) lo = 0;
-        const int rlo = lo < 1 ? 1 : lo;
-        const int totals = hi >= rlo ? hi - rlo + 1 : 0, segs = hi - lo + 1;
-        if (totals > 0) reduce_end += (S - 1) * product_step * bppsa_ceil_div(totals * B, free_units);
-        const double apply_us = generated ? S * 1.4 * bppsa_ceil_div(segs * B, cus)
-                                          : (double)segs * B * S * (128.0 * 128.0 * 4.0) / 4.3e6;
-        cur = (cur > reduce_end ? cur : reduce_end) + totals * totals_step + apply_us;
-        ++slabs;
-        hi = lo - 1;
+  for (int K = k_lo; K <= k_hi; ++K)
+    for (int last = S; last >= S / 4; last /= 2) {
+      if (K < nseg ? (force_last > 0 && last != force_last) : last != S) continue;   // no slab: nothing to cut
+      double cur = (double)(top_steps + (K - 1) * S) * chain_step;
+      int slab = 0, slabs = 0;
+      bool valid = true;
+      if (K < nseg) {
+        const int R = nseg - K;                         // segments R-1 .. 0 lie below the chain
+        slab = force_slab > 0 ? force_slab : free_units / B;
+        if (slab < 1) slab = 1;
+        if (bppsa_ceil_div(R, slab) > BPPSA_H128_MAX_SLABS) slab = bppsa_ceil_div(R, BPPSA_H128_MAX_SLABS);
+        // first pass: when the totals of all slabs are done; second pass: the second stream
+        double reduce_all = 0.0;
+        for (int pass = 0; pass < 2 && valid; ++pass) {
+          double reduce_end = 0.0;
+          slabs = 0;
+          for (int hi = R - 1; hi >= 0;) {
+            const bppsa_h128_slab sl = bppsa_h128_next_slab(hi, slab);
+            int steps = S, totals = sl.hi >= sl.rlo ? sl.hi - sl.rlo + 1 : 0, segs = sl.hi - sl.lo + 1;
+            if (sl.lo == 0 && last < S) {               // the slab farthest from the seed, cut finer
+              segs *= S / last;
+              totals = segs - 1;
+              steps = last;
+              if (segs > BPPSA_H128_FINE_SEGMENTS) valid = false;
+            }
+            if (totals > 0) reduce_end += (steps - 1) * product_step * bppsa_ceil_div(totals * B, free_units);
+            if (pass == 1) {
+              const double start = cur > reduce_end ? cur : reduce_end;
+              // beside the matrix-core kernel the vector kernels get a fraction of their speed
+              const bool beside = start < reduce_all;
+              const double apply_us = generated ? steps * 1.2 * bppsa_ceil_div(segs * B, cus) * (beside ? 1.15 : 1.0)
+                                                : (double)segs * B * steps * (128.0 * 128.0 * 4.0) / 5.3e6 *
+                                                      (beside ? 2.8 : 1.0);
+              cur = start + totals * (beside ? (generated ? 6.0 : 10.0) : totals_step) + apply_us;
+            }
+            ++slabs;
+            hi = sl.lo - 1;
+          }
+          reduce_all = reduce_end;
+        }
+      }
+      if (valid && cur < best_us) {
+        best_us = cur;
+        best = {K, slab, slabs, last, cur};
       }
     }
-    if (cur < best_us) {
-      best_us = cur;
-      best = {K, slab, slabs, cur};
-    }
-  }
   return best;
 }
 

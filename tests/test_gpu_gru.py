@@ -185,6 +185,75 @@ def test_h128_long_scan_matches_oracle_and_replays_in_a_hip_graph(bp, T, B):
         assert torch.equal(G, ref) and torch.equal(g0, ref0)
 
 
+def _near_isometries(T, B, seed_value):
+    import torch
+    H = 128
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(seed_value)
+    Jt = torch.empty((T, B, H, H), dtype=torch.float32, device="cuda")
+    for t0 in range(0, T, 64):                   # identity plus a small random part
+        blk = Jt[t0:t0 + 64]
+        blk.normal_(0.0, 0.03 / np.sqrt(H), generator=gen)
+        blk.diagonal(dim1=-2, dim2=-1).add_(1.0)
+    seed = torch.randn((B, H), dtype=torch.float32, device="cuda", generator=gen)
+    return Jt, seed
+
+
+@pytest.mark.parametrize("T,B,want_g0", [(700, 4, True), (641, 3, False), (130, 5, True)])
+def test_h128_forced_schedules_match_oracle(bp, T, B, want_g0):
+    """Every form of the H=128 schedule on one chain, forced through bppsa_scan_h128_diag: no serial
+    chain (totals of all interior segments, scanned recursively), serial chains of 1, 2, 3 and 5
+    segments with slabs of 1, 2, 3 or all remaining segments, the slab farthest from the seed cut
+    into segments of 64, 32 and 16 steps, and the whole chain walked serially.  T = 641 without g0
+    is ten full segments (no short segment at the seed end); T = 130 has three segments, so that
+    slabs end on segments 1 and 0 in every way.  Every element is compared with the oracle's
+    serial scan."""
+    import torch
+    H = 128
+    Jt, seed = _near_isometries(T, B, 77 + T)
+    G_ref, g0_ref = _oracle_scan_in_chunks(Jt, to_np(seed))
+    ws = torch.empty(bp.scan_workspace_bytes(T, B, H), dtype=torch.uint8, device="cuda")
+    nseg = -(-(T - (0 if want_g0 else 1)) // 64)
+    forms = [(0, 0, 0), (1, 0, 0), (1, 1, 64), (1, 2, 32), (2, 3, 16), (3, 2, 64), (2, 0, 32), (5, 1, 16),
+             (nseg - 1, 0, 0), (nseg - 1, 0, 16), (nseg, 0, 0), (nseg + 3, 0, 0)]
+    for chain, slab, last in forms:
+        G = torch.zeros((T, B, H), dtype=torch.float32, device="cuda")
+        g0 = torch.zeros((B, H), dtype=torch.float32, device="cuda") if want_g0 else None
+        ws.fill_(0xA5)
+        bp.scan_h128_diag(Jt, seed, G=G, g0=g0, workspace=ws, chain_segments=chain, slab_segments=slab,
+                          last_slab_steps=last)
+        torch.cuda.synchronize()
+        what = "chain_segments=%d slab_segments=%d last_slab_steps=%d" % (chain, slab, last)
+        assert torch.equal(G[T - 1], seed), what
+        assert rel_err(to_np(G), G_ref) <= TOL, what
+        assert per_step_err(to_np(G), G_ref) <= 2 * TOL, what
+        if want_g0:
+            assert rel_err(to_np(g0), g0_ref) <= TOL, what
+
+
+def test_h128_diag_rejects_what_it_cannot_run(bp):
+    """Argument checks of bppsa_scan_h128_diag happen on the host, before any launch."""
+    import torch
+    from paper_1907_10134_amd.binding import BppsaError
+    T, B, H = 3000, 2, 128
+    Jt = torch.empty((T, B, H, H), dtype=torch.float32, device="cuda")    # never read
+    seed = torch.zeros((B, H), dtype=torch.float32, device="cuda")
+    G = torch.empty((T, B, H), dtype=torch.float32, device="cuda")
+    ws = torch.empty(bp.scan_workspace_bytes(T, B, H), dtype=torch.uint8, device="cuda")
+    with pytest.raises(BppsaError):          # not a segment length
+        bp.scan_h128_diag(Jt, seed, G=G, workspace=ws, chain_segments=1, last_slab_steps=48)
+    with pytest.raises(BppsaError):          # 46 segments in one slab, cut in two: more than 32 fine segments
+        bp.scan_h128_diag(Jt, seed, G=G, workspace=ws, chain_segments=1, slab_segments=127, last_slab_steps=32)
+    with pytest.raises(BppsaError):
+        bp.scan_h128_diag(Jt, seed, G=G, workspace=ws, chain_segments=-1)
+    with pytest.raises(BppsaError):          # workspace too small
+        bp.scan_h128_diag(Jt, seed, G=G, workspace=ws[:4096], chain_segments=1)
+    Bbig = 200                                # no compute unit per sample beside the matrix-core work
+    Jb = torch.empty((70, Bbig, H, H), dtype=torch.float32, device="cuda")
+    with pytest.raises(BppsaError):
+        bp.scan_h128_diag(Jb, torch.zeros((Bbig, H), device="cuda"), chain_segments=1)
+
+
 def test_h128_long_scan_from_two_host_threads(bp):
     """Two host threads call bppsa_scan at H=128 at the same time, each on its own stream, seed,
     outputs and workspace (the Jacobians are shared, read-only).  Both use the library's second
