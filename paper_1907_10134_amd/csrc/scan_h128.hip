@@ -13,6 +13,16 @@
 
 namespace {
 
+// The value another lane of the same row of 16 lanes holds, without going through LDS: lane i
+// reads lane i ^ 1, i ^ 2 (exact), 7 - i % 8 within its half row, or 15 - i within its row.  The
+// last two flip lane bit 2, resp. 3, together with the bits below it, which is all an exchange
+// between the two halves of a group of lanes needs when only the sum over the group matters.
+constexpr int kDppXor1 = 0xB1, kDppXor2 = 0x4E, kDppHalfMirror = 0x141, kDppMirror = 0x140;
+template <int CTRL>
+__device__ __forceinline__ float dpp_from(float x) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, true));
+}
+
 // P <- J P for J = Jt[hi-1], ..., Jt[lo], starting from P = Jt[hi]; tot[seg][b] = P.
 //
 // v_mfma_f32_32x32x2_f32 contracts two k values per issue: lane l supplies A[i = l % 32][k(l / 32)]
@@ -215,24 +225,28 @@ apply_h128_kernel(int T, int B, int t_min, int S, int seg_begin, const float* __
         for (int q = 0; q < kChunks; ++q) pre[q] = reinterpret_cast<const v4f*>(src)[tid + q * kThreads];
       }
     }
-    // halving exchange over the 32 lanes of the row group: after the step with mask m a lane
-    // keeps the rows whose index bit matches its own lane bit
-#define BPPSA_HALVE(n, m)                                           \
+    // halving exchange over the 32 lanes of the row group: after the step on lane bit k a lane
+    // keeps the rows whose index bit matches its own bit k and has added what its partner (a
+    // lane with the other bit k) held for them.  Bit 4 crosses the rows of 16 lanes and goes
+    // through LDS; the others stay in the vector pipe.
+#define BPPSA_HALVE(n, m, GET)                                      \
     {                                                               \
       const bool upper = (c & (m)) != 0;                            \
       _Pragma("unroll") for (int q = 0; q < (n); ++q) {             \
         const float mine = upper ? part[q + (n)] : part[q];         \
         const float send = upper ? part[q] : part[q + (n)];         \
-        part[q] = mine + __shfl_xor(send, (m));                     \
+        part[q] = mine + GET(send);                                 \
       }                                                             \
     }
-    BPPSA_HALVE(8, 16)
-    BPPSA_HALVE(4, 8)
-    BPPSA_HALVE(2, 4)
-    BPPSA_HALVE(1, 2)
+#define BPPSA_GET16(x) __shfl_xor((x), 16)
+    BPPSA_HALVE(8, 16, BPPSA_GET16)
+    BPPSA_HALVE(4, 8, dpp_from<kDppMirror>)
+    BPPSA_HALVE(2, 4, dpp_from<kDppHalfMirror>)
+    BPPSA_HALVE(1, 2, dpp_from<kDppXor2>)
+#undef BPPSA_GET16
 #undef BPPSA_HALVE
-    // lanes c and c ^ 1 now hold the two halves of row r + 8 * rowsel
-    const float sum = part[0] + __shfl_xor(part[0], 1) + diag;
+    // lanes c and c ^ 1 now hold the two halves of the sum of row `row`
+    const float sum = part[0] + dpp_from<kDppXor1>(part[0]) + diag;
     float* dst = (t >= 1) ? G + ((size_t)(t - 1) * B + b) * H : g0 + (size_t)b * H;
     if ((c & 1) == 0) {
       vs[cur ^ 1][row] = sum;
@@ -256,8 +270,9 @@ constexpr int kChainPieces = HH / 4 / kChainThreads;   // 4
 // partial sums part[q] of rows r + 32 q over the thread's four columns -> the row sum, held by
 // the eight lanes c with the same c / 8; returns the row and leaves the sum in `sum`
 __device__ __forceinline__ int chain_row_sum(float (&part)[kChainPieces], int r, int c, float& sum) {
-  // halving exchange: lane bit 4 keeps the rows with q bit 1 equal to it, lane bit 3 those with
-  // q bit 0; the remaining eight lanes of a row then add up
+  // halving exchange: lane bit 4 keeps the rows with q bit 1 equal to it (through LDS: the partner
+  // is in the other row of 16 lanes), lane bit 3 those with q bit 0; the eight lanes of a half
+  // row then add up
   {
     const bool upper = (c & 16) != 0;
     const float m0 = upper ? part[2] : part[0], s0 = upper ? part[0] : part[2];
@@ -268,12 +283,12 @@ __device__ __forceinline__ int chain_row_sum(float (&part)[kChainPieces], int r,
   {
     const bool upper = (c & 8) != 0;
     const float m0 = upper ? part[1] : part[0], s0 = upper ? part[0] : part[1];
-    part[0] = m0 + __shfl_xor(s0, 8);
+    part[0] = m0 + dpp_from<kDppMirror>(s0);
   }
   sum = part[0];
-  sum += __shfl_xor(sum, 4);
-  sum += __shfl_xor(sum, 2);
-  sum += __shfl_xor(sum, 1);
+  sum += dpp_from<kDppXor1>(sum);
+  sum += dpp_from<kDppXor2>(sum);
+  sum += dpp_from<kDppHalfMirror>(sum);
   return r + 32 * (((c >> 4) & 1) * 2 + ((c >> 3) & 1));
 }
 

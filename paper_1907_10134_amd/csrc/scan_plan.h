@@ -112,7 +112,7 @@ static inline bppsa_h128_plan bppsa_plan_h128(int n, int B, int cus, bool genera
   const int nseg = bppsa_ceil_div(n, S);
   bppsa_h128_plan best = {0, 0, 0, S, 0.0};
   if (cus < 2 * B || nseg < 2) return best;
-  const double chain_step = generated ? 0.80 : 1.40, product_step = generated ? 8.8 : 8.3, totals_step = 1.8;
+  const double chain_step = generated ? 0.78 : 1.40, product_step = generated ? 8.8 : 8.3, totals_step = 1.8;
   const int top_steps = n - (nseg - 1) * S;
   const int free_units = cus - B;                       // the serial chains keep B units to themselves
   double best_us = 1e300;
