@@ -117,10 +117,14 @@ size_t bppsa_scan_workspace_bytes(int T, int B, int H);
  * and registers, Algorithm 1 inside a unit, look-back across units); H = 128 and
  * every other H <= 128 run the hybrid of Section 5.3 (segment totals, scan of
  * the totals, matrix-vector down-sweep); H > 128 yields BPPSA_EUNSUPPORTED.
- * For long chains at H = 128 the matrix-vector kernels are enqueued on a second
- * stream owned by the library (one per device, created on first use) and tied
- * to `stream` with events on both sides: work enqueued on `stream` after the
- * call still sees every result, and the call can be captured into a HIP graph.
+ * At H = 128, chains longer than one segment are scheduled by a cost model
+ * (bppsa_scan_h128_schedule shows its choice): the steps nearest the seed are
+ * walked by a serial matrix-vector chain per sample while the totals of the
+ * other segments are formed on the matrix cores.  The chain and the
+ * matrix-vector kernels are enqueued on a second stream owned by the library
+ * (one per device, created on first use) and tied to `stream` with events on
+ * both sides: work enqueued on `stream` after the call still sees every
+ * result, and the call can be captured into a HIP graph.
  * The workspace is scratch only; its contents before the call do not matter.
  * For H = 20 its first 4-byte word is an error flag: it is 0 after a normal
  * call and 1 if a bounded wait inside the kernel expired, in which case G is
