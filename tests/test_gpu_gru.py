@@ -231,6 +231,19 @@ def test_h128_forced_schedules_match_oracle(bp, T, B, want_g0):
             assert rel_err(to_np(g0), g0_ref) <= TOL, what
 
 
+def test_h128_many_slabs(bp):
+    """A chain cut into the largest number of slabs the launcher handles (a forced slab of one
+    segment is raised to two: 31 slabs, one event each), against the oracle's serial scan."""
+    import torch
+    T, B, H = 4000, 8, 128
+    Jt, seed = _near_isometries(T, B, 4242)
+    G = bp.scan_h128_diag(Jt, seed, chain_segments=2, slab_segments=1, last_slab_steps=64)
+    torch.cuda.synchronize()
+    G_ref, _ = _oracle_scan_in_chunks(Jt, to_np(seed))
+    assert rel_err(to_np(G), G_ref) <= TOL
+    assert per_step_err(to_np(G), G_ref) <= 2 * TOL
+
+
 def test_h128_diag_rejects_what_it_cannot_run(bp):
     """Argument checks of bppsa_scan_h128_diag happen on the host, before any launch."""
     import torch
@@ -310,7 +323,8 @@ def _fused_vs_oracle(bp, w, want_g0=True):
     return h, seed, to_np(G), None if g0 is None else to_np(g0)
 
 
-@pytest.mark.parametrize("T,B,I", [(7, 5, 1), (64, 2, 3), (65, 3, 1), (70, 2, 1), (300, 3, 2), (1000, 2, 1), (129, 33, 1)])
+@pytest.mark.parametrize("T,B,I", [(7, 5, 1), (64, 2, 3), (65, 3, 1), (70, 2, 1), (300, 3, 2), (1000, 2, 1), (129, 33, 1),
+                                   (200, 130, 1)])
 def test_gru_scan_fused_matches_oracle_chain(bp, T, B, I):
     """bppsa_gru_scan_fused (Jacobians generated inside the scan's kernels) against the oracle's
     matrix-free chain, every element; sizes cover one segment, a ragged last segment, the chain of
