@@ -278,6 +278,17 @@ def gru_workload(bp, workloads, steps):
     torch.cuda.synchronize()
     parts = {name: statistics.mean(e[i].elapsed_time(e[i + 1]) for e in evs)
              for i, name in enumerate(("build_jacobians_ms", "scan_ms", "param_grads_ms"))}
+    # the same scan without the serial chain (totals of all interior segments, scanned recursively)
+    two_level = lambda: bp.scan_h128_diag(Jt, seed, G=G, workspace=ws, chain_segments=0)
+    two_level()
+    torch.cuda.synchronize()
+    tev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    for a, z in tev:
+        a.record()
+        two_level()
+        z.record()
+    torch.cuda.synchronize()
+    two_level_ms = statistics.mean(a.elapsed_time(z) for a, z in tev)
     sched = bp.scan_h128_schedule(T, B, want_g0=False, generated=False)
     fsched = bp.scan_h128_schedule(T, B, want_g0=False, generated=True)
     mm = sched["matrix_products"]
@@ -298,7 +309,7 @@ def gru_workload(bp, workloads, steps):
     torch.cuda.synchronize()
     fused_ms = statistics.mean(a.elapsed_time(z) for a, z in fev)
     return {"workload": "gru_H128_I1_T4096_B16 (configs[3])", **{k: round(v, 4) for k, v in parts.items()},
-            "fused_scan_ms": round(fused_ms, 4),
+            "fused_scan_ms": round(fused_ms, 4), "two_level_scan_ms": round(two_level_ms, 4),
             "fused_vs_build_plus_scan": round((parts["build_jacobians_ms"] + parts["scan_ms"]) / fused_ms, 3),
             "schedule": {k: sched[k] for k in ("segment_steps", "chain_steps", "slab_segments", "slabs", "last_slab_steps")},
             "fused_schedule": {k: fsched[k] for k in ("segment_steps", "chain_steps", "slab_segments", "slabs", "last_slab_steps",
