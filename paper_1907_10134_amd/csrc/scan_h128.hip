@@ -5,7 +5,8 @@
 // kernel keeps the running product of a segment in registers, as MFMA results that are the next
 // step's B operands, and streams one transposed Jacobian per step through LDS; the apply kernel
 // walks a segment with matrix-vector products (the down-sweep side), streaming each Jacobian
-// once with the next one already in flight.
+// once with the next one already in flight; the chain kernels walk the stretch of a long chain
+// nearest the seed, which needs no matrix-matrix product at all, one workgroup per sample.
 //
 // This file is compiled with MFMA results in ordinary vector registers (see the build script):
 // an accumulation register cannot be a B operand.

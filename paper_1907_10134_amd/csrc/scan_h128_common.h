@@ -25,11 +25,13 @@ __device__ __forceinline__ void seg_bounds(int T, int t_min, int S, int seg, int
 // GRU transposed Jacobians generated in place of being read (Appendix E):
 //   Jt[i][j] = W_hr[j][i] a_j + W_hn[j][i] c_j + W_hz[j][i] e_j + [i == j] z_j
 // with the per-step coefficient vectors (a, c, e, z) of bppsa_gru_coefs_h128 and the three
-// recurrent matrices transposed, wT[g][i][j] (g = r, n, z).  Both kernels below give thread tid
-// the 16-byte pieces e = tid + 256 q of a tile, i.e. rows tid / 32 + 8 q and columns
+// recurrent matrices transposed, wT[g][i][j] (g = r, n, z).  The 256-thread kernels give thread
+// tid the 16-byte pieces e = tid + 256 q of a tile, i.e. rows tid / 32 + 8 q and columns
 // 4 (tid % 32) .. + 3: the same places in every tile, so the thread keeps its 3 x 16 pieces of
-// the weights in registers for the whole segment and a tile costs it four coefficient reads and
-// 192 multiply-adds instead of 256 bytes from HBM.
+// the weights in registers for the whole segment.  Where the tile itself is needed (the A
+// operand of a matrix-matrix step) it costs the thread four coefficient reads and 192
+// multiply-adds instead of 256 bytes from HBM; where only its product with a vector is needed,
+// the three weight matrices are applied to the vector scaled by a, c and e and no tile is formed.
 struct GruWeights {
   v4f r[kChunks], n[kChunks], z[kChunks];
 };
