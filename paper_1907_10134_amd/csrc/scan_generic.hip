@@ -261,8 +261,9 @@ bppsa_status scan_h128_pipelined(int T, int B, int t_min, int S, int nseg, const
       if (top >= rlo) {
         // svin[seg-1] = stot[seg] svin[seg] for seg = top .. rlo: the totals as a chain of
         // top-rlo+1 steps, entered by svin[top]; also gives the next slab its entering vector
-        e = launch_apply(top + 1, B, H, rlo, top - rlo + 1, 0, 1, stot, svin + (size_t)top * row, 1, svin, nullptr,
-                         nullptr, s2);
+        // (on the compute units the serial chain has left: beside the matrix-core kernel a
+        // 256-thread workgroup would take 6 to 10 us per step)
+        e = bppsa_chain_h128(B, rlo, top, stot, svin + (size_t)top * row, svin, nullptr, nullptr, s2, nullptr);
         if (e != BPPSA_OK) return e;
       }
       e = launch_apply(svin == vin ? T : t_min + (top + 1) * steps, B, H, t_min, steps, lo, top - lo + 1, Jt, svin, 0, G,

@@ -112,7 +112,7 @@ static inline bppsa_h128_plan bppsa_plan_h128(int n, int B, int cus, bool genera
   const int nseg = bppsa_ceil_div(n, S);
   bppsa_h128_plan best = {0, 0, 0, S, 0.0};
   if (cus < 2 * B || nseg < 2) return best;
-  const double chain_step = generated ? 0.78 : 1.40, product_step = generated ? 8.8 : 8.3, totals_step = 1.8;
+  const double chain_step = generated ? 0.70 : 1.40, product_step = generated ? 8.8 : 8.3, totals_step = 1.2;
   const int top_steps = n - (nseg - 1) * S;
   const int free_units = cus - B;                       // the serial chains keep B units to themselves
   double best_us = 1e300;
@@ -145,13 +145,16 @@ static inline bppsa_h128_plan bppsa_plan_h128(int n, int B, int cus, bool genera
             }
             if (totals > 0) reduce_end += (steps - 1) * product_step * bppsa_ceil_div(totals * B, free_units);
             if (pass == 1) {
-              const double start = cur > reduce_end ? cur : reduce_end;
-              // beside the matrix-core kernel the vector kernels get a fraction of their speed
+              double start = (cur > reduce_end ? cur : reduce_end) + totals * totals_step;
+              // Beside the matrix-core kernel the matrix-vector pass on stored Jacobians gets a
+              // fraction of its speed; the pass on generated ones (242 registers) does not fit on a
+              // compute unit beside the totals kernel of that form (313) and waits for it.
               const bool beside = start < reduce_all;
-              const double apply_us = generated ? steps * 1.2 * bppsa_ceil_div(segs * B, cus) * (beside ? 1.15 : 1.0)
+              if (generated && beside) start = reduce_all;
+              const double apply_us = generated ? steps * 1.1 * bppsa_ceil_div(segs * B, cus)
                                                 : (double)segs * B * steps * (128.0 * 128.0 * 4.0) / 5.3e6 *
                                                       (beside ? 2.8 : 1.0);
-              cur = start + totals * (beside ? (generated ? 6.0 : 10.0) : totals_step) + apply_us;
+              cur = start + apply_us;
             }
             ++slabs;
             hi = sl.lo - 1;
