@@ -112,6 +112,16 @@ static inline bppsa_h128_plan bppsa_plan_h128(int n, int B, int cus, bool genera
   const int nseg = bppsa_ceil_div(n, S);
   bppsa_h128_plan best = {0, 0, 0, S, 0.0};
   if (cus < 2 * B || nseg < 2) return best;
+  // the search below is O(segments x slabs): a training loop asks for the same sizes every
+  // iteration, so each host thread remembers its last answer
+  struct Memo {
+    int n, B, cus, generated, force_chain, force_slab, force_last;
+    bppsa_h128_plan plan;
+  };
+  static thread_local Memo memo = {-1, 0, 0, 0, 0, 0, 0, {0, 0, 0, 0, 0.0}};
+  if (memo.n == n && memo.B == B && memo.cus == cus && memo.generated == (int)generated &&
+      memo.force_chain == force_chain && memo.force_slab == force_slab && memo.force_last == force_last)
+    return memo.plan;
   const double chain_step = generated ? 0.70 : 1.40, product_step = generated ? 8.8 : 8.3, totals_step = 1.2;
   const int top_steps = n - (nseg - 1) * S;
   const int free_units = cus - B;                       // the serial chains keep B units to themselves
@@ -167,6 +177,7 @@ static inline bppsa_h128_plan bppsa_plan_h128(int n, int B, int cus, bool genera
         best = {K, slab, slabs, last, cur};
       }
     }
+  memo = Memo{n, B, cus, (int)generated, force_chain, force_slab, force_last, best};
   return best;
 }
 
