@@ -171,8 +171,10 @@ bppsa_status bppsa_rnn_scan_fused(int T, int B, int H, const float* h, const flo
  * The GRU counterpart for H = 128 (the size of Section 4.2's workload): the scan with the
  * transposed Jacobians of Appendix E's closed form generated inside its kernels from the
  * hidden states, the inputs and the weights, so no [T,B,H,H] array exists.  A first kernel
- * recomputes the gates of every step and keeps four H-vectors per step; the kernels of the scan
- * then form each Jacobian from those and the three recurrent matrices held in registers.
+ * recomputes the gates of every step and keeps four H-vectors per step; where the scan needs a
+ * Jacobian as a matrix (the A operand of a matrix-matrix step) its kernel forms it from those
+ * and the three recurrent matrices held in registers, and where it needs a Jacobian times a
+ * vector it applies the three matrices to the vector scaled by those vectors instead.
  * Arguments as for bppsa_build_jacobians (cell GRU) followed by bppsa_scan; the result equals
  * those two calls up to rounding.  workspace: at least bppsa_gru_scan_fused_workspace_bytes
  * bytes (0 for sizes it does not serve), 256-byte aligned.  Other H: BPPSA_EUNSUPPORTED.
