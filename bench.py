@@ -248,6 +248,13 @@ def gru_workload(bp, workloads, steps):
     d = {k: torch.from_numpy(w[k]).cuda() for k in ("x", "w_ih", "w_hh", "b_ih", "b_hh", "w_out", "b_out", "labels")}
     h = torch.zeros((T + 1, B, H), dtype=torch.float32, device="cuda")
     bp.forward(bp.GRU, d["x"], d["w_ih"], d["w_hh"], d["b_ih"], d["b_hh"], h)
+    torch.cuda.synchronize()
+    fw = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+    fw[0].record()
+    bp.forward(bp.GRU, d["x"], d["w_ih"], d["w_hh"], d["b_ih"], d["b_hh"], h)   # not part of the backward pass
+    fw[1].record()
+    torch.cuda.synchronize()
+    forward_ms = fw[0].elapsed_time(fw[1])
     seed, _ = bp.head_seed(h[-1].contiguous(), d["w_out"], d["b_out"], d["labels"])
     Jt = torch.empty((T, B, H, H), dtype=torch.float32, device="cuda")
     G = torch.empty((T, B, H), dtype=torch.float32, device="cuda")
@@ -310,6 +317,7 @@ def gru_workload(bp, workloads, steps):
     fused_ms = statistics.mean(a.elapsed_time(z) for a, z in fev)
     return {"workload": "gru_H128_I1_T4096_B16 (configs[3])", **{k: round(v, 4) for k, v in parts.items()},
             "fused_scan_ms": round(fused_ms, 4), "two_level_scan_ms": round(two_level_ms, 4),
+            "forward_ms": round(forward_ms, 4),
             "fused_vs_build_plus_scan": round((parts["build_jacobians_ms"] + parts["scan_ms"]) / fused_ms, 3),
             "schedule": {k: sched[k] for k in ("segment_steps", "chain_steps", "slab_segments", "slabs", "last_slab_steps")},
             "fused_schedule": {k: fsched[k] for k in ("segment_steps", "chain_steps", "slab_segments", "slabs", "last_slab_steps",

@@ -292,6 +292,114 @@ gru_param_partials_h128_kernel(long long rows, int I, int nsplit, long long rows
   }
 }
 
+// ---- the recurrence itself (bppsa_forward, GRU, H = 128) -------------------------------------------
+// One workgroup of 1024 threads per sample walks the sequence.  Thread (r, c) = (tid / 32, tid % 32)
+// keeps columns 4c..4c+3 of rows r, r+32, r+64, r+96 of W_hr, W_hz and W_hn in registers (48 values),
+// multiplies them with its four entries of the state, and the 32 partial sums of a row meet in one
+// LDS exchange (across rows of 16 lanes) and four DPP exchanges; the 128 threads that own a hidden
+// unit then add the input part and the biases and apply the gates (Section 4.2).  A step costs two
+// workgroup barriers and reads no weight from memory.
+constexpr int kFwdThreads = 1024;
+constexpr int kFwdMaxI = 8;
+
+template <int CTRL>
+__device__ __forceinline__ float fwd_dpp(float x) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, true));
+}
+
+// part[q] = partial sum of row r + 32 q over the thread's four columns -> the sum of one row over all
+// 128 columns, in each of the eight lanes c with the same c / 8; that row is
+// r + 32 (2 (c / 16) + (c / 8) % 2).  (DPP controls: 0x140 row mirror, 0xB1 / 0x4E quad permutations
+// [1,0,3,2] / [2,3,0,1], 0x141 half-row mirror; a partner with other low lane bits serves as well as
+// the exact one, since only the sum over the group is wanted.)
+__device__ __forceinline__ float fwd_row_sum(float (&part)[4], int c) {
+  {
+    const bool upper = (c & 16) != 0;
+    const float m0 = upper ? part[2] : part[0], s0 = upper ? part[0] : part[2];
+    const float m1 = upper ? part[3] : part[1], s1 = upper ? part[1] : part[3];
+    part[0] = m0 + __shfl_xor(s0, 16);
+    part[1] = m1 + __shfl_xor(s1, 16);
+  }
+  {
+    const bool upper = (c & 8) != 0;
+    const float m0 = upper ? part[1] : part[0], s0 = upper ? part[0] : part[1];
+    part[0] = m0 + fwd_dpp<0x140>(s0);
+  }
+  float sum = part[0];
+  sum += fwd_dpp<0xB1>(sum);
+  sum += fwd_dpp<0x4E>(sum);
+  sum += fwd_dpp<0x141>(sum);
+  return sum;
+}
+
+__global__ void __launch_bounds__(kFwdThreads)
+gru_forward_h128_kernel(int T, int B, int I, const float* __restrict__ x, const float* __restrict__ w_ih,
+                        const float* __restrict__ w_hh, const float* __restrict__ b_ih,
+                        const float* __restrict__ b_hh, float* __restrict__ h) {
+  __shared__ __attribute__((aligned(16))) float hs[2][H];
+  __shared__ float gh[3][H];
+  const int tid = threadIdx.x;
+  const int c = tid & 31, r = tid >> 5;
+  const int b = blockIdx.x;
+  v4f w[3][4];
+#pragma unroll
+  for (int g = 0; g < 3; ++g)
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+      w[g][q] = *reinterpret_cast<const v4f*>(w_hh + (size_t)(g * H + r + 32 * q) * H + 4 * c);
+  const int row = r + 32 * (((c >> 4) & 1) * 2 + ((c >> 3) & 1));
+  // the threads that own a hidden unit: biases, input weights, and the inputs of the next step
+  const int j = tid < H ? tid : 0;
+  float bi[3], bh[3], wi[3][kFwdMaxI], xs[kFwdMaxI];
+#pragma unroll
+  for (int g = 0; g < 3; ++g) {
+    bi[g] = b_ih ? b_ih[g * H + j] : 0.f;
+    bh[g] = b_hh ? b_hh[g * H + j] : 0.f;
+#pragma unroll
+    for (int i = 0; i < kFwdMaxI; ++i) wi[g][i] = i < I ? w_ih[(size_t)(g * H + j) * I + i] : 0.f;
+  }
+#pragma unroll
+  for (int i = 0; i < kFwdMaxI; ++i) xs[i] = i < I ? x[(size_t)b * I + i] : 0.f;     // x[0][b]
+  if (tid < H) hs[0][tid] = h[(size_t)b * H + tid];
+  __syncthreads();
+  int cur = 0;
+  for (int t = 1; t <= T; ++t) {
+    const v4f hv = *reinterpret_cast<const v4f*>(&hs[cur][4 * c]);
+#pragma unroll
+    for (int g = 0; g < 3; ++g) {
+      float part[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        part[q] = (w[g][q][0] * hv[0] + w[g][q][1] * hv[1]) + (w[g][q][2] * hv[2] + w[g][q][3] * hv[3]);
+      const float sum = fwd_row_sum(part, c);
+      if ((c & 7) == 0) gh[g][row] = sum;
+    }
+    float xn[kFwdMaxI];
+#pragma unroll
+    for (int i = 0; i < kFwdMaxI; ++i) xn[i] = (i < I && t < T) ? x[((size_t)t * B + b) * I + i] : 0.f;
+    __syncthreads();
+    if (tid < H) {
+      float ai[3];
+#pragma unroll
+      for (int g = 0; g < 3; ++g) {
+        ai[g] = bi[g];
+#pragma unroll
+        for (int i = 0; i < kFwdMaxI; ++i) ai[g] += wi[g][i] * xs[i];
+      }
+      const float rr = sigmoidf_(ai[0] + (gh[0][tid] + bh[0]));
+      const float zz = sigmoidf_(ai[1] + (gh[1][tid] + bh[1]));
+      const float nn = tanhf(ai[2] + rr * (gh[2][tid] + bh[2]));
+      const float hn = (1.f - zz) * nn + zz * hs[cur][tid];
+      hs[cur ^ 1][tid] = hn;
+      h[((size_t)t * B + b) * H + tid] = hn;
+    }
+#pragma unroll
+    for (int i = 0; i < kFwdMaxI; ++i) xs[i] = xn[i];
+    __syncthreads();
+    cur ^= 1;
+  }
+}
+
 }  // namespace
 
 bppsa_status bppsa_build_jacobians_gru_h128(int T, int B, int I, const float* h, const float* x,
@@ -344,6 +452,14 @@ bppsa_status bppsa_gru_param_partials_h128(long long rows, int I, int nsplit, co
   rps = (rps + 1) / 2 * 2;
   gru_param_partials_h128_kernel<<<dim3(3 * H / 32, (nsplit + 3) / 4), 256, 0, stream>>>(rows, I, nsplit, rps, h, x,
                                                                                          delta, part);
+  BPPSA_CHECK_LAUNCH();
+  return BPPSA_OK;
+}
+
+bppsa_status bppsa_gru_forward_h128(int T, int B, int I, const float* x, const float* w_ih, const float* w_hh,
+                                    const float* b_ih, const float* b_hh, float* h, hipStream_t stream) {
+  if (I > kFwdMaxI) return BPPSA_EUNSUPPORTED;
+  gru_forward_h128_kernel<<<B, kFwdThreads, 0, stream>>>(T, B, I, x, w_ih, w_hh, b_ih, b_hh, h);
   BPPSA_CHECK_LAUNCH();
   return BPPSA_OK;
 }

@@ -4,6 +4,10 @@
 // simplicity: one workgroup per sample walks the sequence.
 #include "bppsa_internal.h"
 
+// the GRU recurrence for H = 128 and at most 8 input features (weights in registers)
+bppsa_status bppsa_gru_forward_h128(int T, int B, int I, const float* x, const float* w_ih, const float* w_hh,
+                                    const float* b_ih, const float* b_hh, float* h, hipStream_t stream);
+
 namespace {
 
 __device__ __forceinline__ float sigmoidf_(float a) { return 1.0f / (1.0f + expf(-a)); }
@@ -227,6 +231,7 @@ extern "C" bppsa_status bppsa_forward(int cell, int T, int B, int H, int I,
     }
   } else if (cell == BPPSA_GRU) {
     if (3 * H > 1024) return BPPSA_ESHAPE;
+    if (H == 128 && I <= 8) return bppsa_gru_forward_h128(T, B, I, x, w_ih, w_hh, b_ih, b_hh, h, s);
     const int nt = bppsa_ceil_div(3 * H, 64) * 64;
     gru_forward_kernel<<<B, nt, 7 * H * sizeof(float), s>>>(T, B, H, I, x, w_ih, w_hh, b_ih, b_hh, h);
   } else {
