@@ -135,13 +135,16 @@ def _oracle_scan_in_chunks(Jt, seed, chunk=64):
     return G, g
 
 
-@pytest.mark.parametrize("T,B", [(2304, 16), (700, 64), (11000, 3), (260, 256)])
+@pytest.mark.parametrize("T,B", [(2304, 16), (700, 64), (11000, 3), (260, 256), (200, 128), (450, 1)])
 def test_h128_long_scan_matches_oracle_and_replays_in_a_hip_graph(bp, T, B):
-    """Chains long enough for the form of the H=128 scan that runs its matrix-matrix and its
-    matrix-vector kernels side by side on two streams (2 to 4 GB of Jacobians; slabs of 16, 4, 85
-    and 1 segments, a clamped slab count at B=3, a partial last slab everywhere).  Every element
-    of G and g0 is compared with the oracle's serial scan of the same chain; repeated calls and
-    replays of a captured graph return the same bits whatever the workspace held."""
+    """The H=128 scan as its cost model schedules it, on chains of several shapes (up to 4 GB of
+    Jacobians): a serial chain beside two slabs of 15 segments (B=16), beside one slab of 3 (B=64),
+    beside two slabs of 84 (B=3); the two-level form without a serial chain where the batch alone
+    fills the device (B=256); the largest batch that still gets a compute unit per sample (B=128,
+    T=200: the model walks the whole chain serially) and a single sample (a short chain, then one
+    slab cut into 16-step segments).  Every element of G and g0 is
+    compared with the oracle's serial scan of the same chain; repeated calls and replays of a
+    captured graph return the same bits whatever the workspace held."""
     import torch
     H = 128
     gen = torch.Generator(device="cuda")
