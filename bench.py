@@ -324,6 +324,10 @@ def gru_workload(bp, workloads, steps):
                                                       "matrix_products")},
             "scan_matrix_products": mm, "scan_flop": flop, "scan_tflops": round(tf, 2),
             "frac_of_fp32_mfma_peak": round(tf / 157.3, 4),
+            "two_level_frac_of_fp32_mfma_peak": round(
+                ((T - 1 + 63) // 64 - 2) * 63 * B * 2 * H ** 3 / (two_level_ms * 1e-3) / 1e12 / 157.3, 4),
+            "note": "scan_tflops counts the products the schedule executes; the serial chain removes products, "
+                    "so compare scan_ms with two_level_scan_ms, not the rates",
             "scan_bytes_min": T * B * (4 * H * H + 4 * H), "jacobian_bytes": 4 * T * B * H * H}
 
 
@@ -654,7 +658,8 @@ def main():
         # serial chain makes fewer: compare times, not this rate, across schedules
         out["gru"] = {k: g[k] for k in ("workload", "build_jacobians_ms", "scan_ms", "param_grads_ms",
                                         "fused_scan_ms", "two_level_scan_ms", "schedule", "scan_matrix_products",
-                                        "scan_tflops", "frac_of_fp32_mfma_peak")}
+                                        "scan_tflops", "frac_of_fp32_mfma_peak", "two_level_frac_of_fp32_mfma_peak",
+                                        "note")}
         torch.cuda.empty_cache()
         c = cnn_workload(bp, workloads, 10)
         out["cnn"] = {"workload": c["workload"], "nnz": c["nnz"], "build_all_jacobians_ms": c["build_all_jacobians_ms"],
